@@ -1,0 +1,171 @@
+/*
+ * halo.h -- C ABI of the MI355X (gfx950) HALO low-precision linear layer.
+ *
+ * HALO (Hadamard-Assisted Lower-Precision Optimization) runs the three matrix products of a
+ * linear layer in INT8:
+ *      F:  Y   = X  W^T      (Section 2, Eq. 1a)        X [b x m], W [n x m], Y [b x n]
+ *      G:  G   = E^T X       (Section 2, Eq. 1b)        E = E_Y [b x n], G [n x m]
+ *      E:  E_X = E  W        (Section 2, Eq. 1c)        E_X [b x m]
+ * with Walsh-Hadamard rotations placed according to the HALO level (Appendix, Table "HALO
+ * levels"; Section 3.3).  Every operand is quantised with a symmetric absmax scale per row of
+ * the GEMM operand, round-to-nearest-even, codes in [-127, 127].
+ *
+ * Conventions for every entry point
+ *   - All data pointers are DEVICE pointers (HIP device memory of the current device).  The
+ *     caller owns every buffer; the library never allocates, frees or synchronises.  All work
+ *     is enqueued on `stream` (a hipStream_t passed as void*; NULL = the default stream).
+ *   - Matrices are row-major.  A leading dimension `ld*` is in ELEMENTS of that matrix and the
+ *     buffer must span rows*ld elements.  Data pointers must be 16-byte aligned and
+ *     ld*sizeof(element) must be a multiple of 16, else HALO_EALIGN.
+ *   - Arguments are checked on the host before anything is launched; a failed check returns an
+ *     error code and enqueues nothing.  HIP launch failures return HALO_EHIP.
+ *   - Same inputs give bit-identical outputs (no result depends on atomic ordering).
+ *   - A Hadamard block size is 0 (no rotation) or a power of two in [2, 4096] (right-hand, along
+ *     the contiguous axis) / [2, 65536] (left-hand, along the strided axis) that divides the axis
+ *     length; the rotation is block-diagonal, I (x) H_block, when the block is shorter than the
+ *     axis.  H_block is the normalised Walsh-Hadamard matrix of the recursion H_d = H_2 (x) H_{d/2}
+ *     (Section 2, "Hadamard Transformations"); its butterflies run in ascending stride order
+ *     in fp32 and the 1/sqrt(block) factor is applied once at the end.
+ */
+#ifndef HALO_H
+#define HALO_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    HALO_OK = 0,
+    HALO_EINVAL = 1,        /* null pointer, negative size, unknown enum value            */
+    HALO_ESHAPE = 2,        /* sizes that do not fit together (block does not divide, ld) */
+    HALO_EALIGN = 3,        /* pointer or leading dimension not 16-byte aligned           */
+    HALO_EWORKSPACE = 4,    /* workspace missing or smaller than *_workspace_bytes()      */
+    HALO_EUNSUPPORTED = 5,  /* valid request this build has no kernel for                 */
+    HALO_EHIP = 6           /* a HIP call failed                                          */
+} halo_status;
+
+typedef enum { HALO_BF16 = 0, HALO_F32 = 1 } halo_dtype;
+typedef enum { HALO_LEVEL0 = 0, HALO_LEVEL1 = 1, HALO_LEVEL2 = 2 } halo_level;
+
+typedef enum {
+    HALO_QUANT_ROWS = 0,    /* one scale per row of `in`; codes keep the layout of `in`            */
+    HALO_QUANT_COLS_T = 1   /* one scale per column of `in`; codes are written TRANSPOSED [cols x rows] */
+} halo_axis;
+
+const char* halo_status_string(halo_status s);
+int halo_version(void);
+
+/* ---------------------------------------------------------------------------------------------
+ * halo_hadamard_quant: rotate -> fold -> absmax -> INT8.       (Section 2: h(A) = A H, h'(A) = H^T A;
+ * Section 4 setup: symmetric round-to-nearest quantiser; Table "HALO levels": (XH)_Q, (WH)_Q, (E_Y)_Q,
+ * (H E_Y)_Q, (E_Y^T)_Q.)
+ *
+ *   in            [rows x cols], bf16 or fp32, leading dimension ld_in.
+ *   had_block     right-hand rotation along each row (0 = none).
+ *   had_block_left left-hand rotation down each column (0 = none).  Needs workspace.
+ *   fold          optional fp32 vector multiplied into the rotated values before the absmax; it is
+ *                 indexed along the axis the scales do NOT run over (length cols for
+ *                 HALO_QUANT_ROWS, length rows for HALO_QUANT_COLS_T).  This is how the saved per-row
+ *                 scales of (WH)_Q / (XH)_Q enter the backward GEMMs.  NULL = none.
+ *   HALO_QUANT_ROWS:   v = rotate(in) * fold[k];  amax_r = max_k |v[r,k]|;
+ *                      out_q[r*ld_q + k] = rint(v * (127/amax_r)), out_scale[r] = amax_r/127
+ *                      (amax_r == 0: codes 0, scale 1).
+ *   HALO_QUANT_COLS_T: v = in * fold[r];  amax_k = max_r |v[r,k]|;
+ *                      out_q[k*ld_q + r] = rint(v * (127/amax_k)), out_scale[k] = amax_k/127.
+ *                      Rotations are not available on this axis (HALO_EUNSUPPORTED).
+ *   out_q         int8, leading dimension ld_q (>= cols, resp. >= rows).
+ *   out_scale     fp32, one per row (resp. per column).
+ *   workspace     device scratch of at least halo_hadamard_quant_workspace_bytes(...) bytes
+ *                 (may be NULL when that is 0).
+ * rows == 0 or cols == 0 is a no-op returning HALO_OK.
+ */
+size_t halo_hadamard_quant_workspace_bytes(int64_t rows, int64_t cols, halo_axis axis,
+                                           int32_t had_block_left);
+
+halo_status halo_hadamard_quant(const void* in, halo_dtype in_dt, int64_t rows, int64_t cols,
+                                int64_t ld_in, halo_axis axis, int32_t had_block,
+                                int32_t had_block_left, const float* fold, int8_t* out_q,
+                                int64_t ld_q, float* out_scale, void* workspace,
+                                size_t workspace_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * halo_gemm_i8: INT8 GEMM with int32 accumulation and a scaling epilogue.   (Section 2, Eqs. 1a-1c on
+ * quantised operands; Table "HALO levels".)
+ *
+ *   acc[i,j] = sum_k A[i,k] * opB[k,j]          exact in int32 (caller keeps 127*127*K < 2^31)
+ *   C[i,j]   = (float(acc[i,j]) * row_scale[i]) * col_scale[j]      rounded to c_dt
+ *
+ *   A        int8 [M x K], leading dimension lda (K contiguous).
+ *   B        transB != 0: int8 [N x K], ldb  (K contiguous; C = A B^T, the forward product)
+ *            transB == 0: int8 [K x N], ldb  (K strided;    C = A B,   both backward products)
+ *   K        must be a multiple of 16 (HALO_ESHAPE otherwise); M, N arbitrary.
+ *   row_scale [M], col_scale [N]   fp32, each may be NULL (= 1).
+ *   C        bf16 or fp32 [M x N], ldc; may be NULL if only acc_out is wanted.
+ *   acc_out  optional int32 [M x N], ld_acc: the raw accumulators.
+ * At least one of C / acc_out must be non-NULL.  M, N or K == 0: no-op (K == 0 writes zeros).
+ */
+halo_status halo_gemm_i8(const int8_t* A, int64_t lda, const int8_t* B, int64_t ldb, int transB,
+                         int64_t M, int64_t N, int64_t K, const float* row_scale,
+                         const float* col_scale, void* C, halo_dtype c_dt, int64_t ldc,
+                         int32_t* acc_out, int64_t ld_acc, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * halo_dequant_unrotate: the tail of both backward products.   (Table "HALO levels": the trailing H^T
+ * of  (E_Y)_Q (WH)_Q H^T  and  (E_Y^T)_Q (XH)_Q H^T,  and the leading H^T of level 2.)
+ *
+ *   T[r,k] = float(acc[r,k]) * row_scale[r];   T <- T (I (x) H_had_block)   (right-hand, if had_block)
+ *   T <- (I (x) H_had_block_left)^T T          (left-hand, if had_block_left);   out = T rounded to out_dt.
+ *
+ *   acc int32 [rows x cols] ld_acc; row_scale fp32 [rows] or NULL; out bf16/fp32 [rows x cols] ld_out.
+ *   workspace: halo_dequant_unrotate_workspace_bytes(rows, cols, had_block_left) bytes.
+ */
+size_t halo_dequant_unrotate_workspace_bytes(int64_t rows, int64_t cols, int32_t had_block_left);
+
+halo_status halo_dequant_unrotate(const int32_t* acc, int64_t ld_acc, int64_t rows, int64_t cols,
+                                  const float* row_scale, int32_t had_block, int32_t had_block_left,
+                                  void* out, halo_dtype out_dt, int64_t ld_out, void* workspace,
+                                  size_t workspace_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * The layer.  (Table "HALO levels"; Section 3.2 Steps 1-3; Section 3.3.)
+ *
+ *   level 0:  F = X_Q W_Q^T          E = (E_Y)_Q W_Q                     G = (E_Y^T)_Q X_Q
+ *   level 1:  F = (XH)_Q (WH)_Q^T    E = (E_Y)_Q (WH)_Q H^T              G = (E_Y^T)_Q (XH)_Q H^T
+ *   level 2:  F = (XH)_Q (WH)_Q^T    E = H^T (H E_Y)_Q (WH)_Q H^T        G = (E_Y^T)_Q (XH)_Q H^T
+ *
+ *   b, m, n        tokens, in-features, out-features.  m and n multiples of 16, b a multiple of 16.
+ *   had_block_m    right-hand block over m; 0 = largest power of two dividing m, capped at 4096.
+ *   had_block_b    left-hand block over b (level 2 only); 0 = largest power of two dividing b.
+ *   out_dt         type of Y, E_X and G.
+ */
+typedef struct halo_linear_desc {
+    int64_t b, m, n;
+    int32_t level;          /* halo_level */
+    int32_t had_block_m;
+    int32_t had_block_b;
+    int32_t out_dt;         /* halo_dtype */
+} halo_linear_desc;
+
+size_t halo_linear_workspace_bytes(const halo_linear_desc* desc);
+
+/* Forward.  X bf16 [b x m] (ld m), W bf16 [n x m] (ld m), Y [b x n] (ld n).
+ * Xq int8 [b x m], s_x fp32 [b], Wq int8 [n x m], s_w fp32 [n] are the saved-for-backward tensors
+ * (Section 3.2 Step 2), always caller-allocated.  If X is NULL, Xq/s_x are taken as already holding
+ * (XH)_Q (e.g. q/k/v share one activation); likewise W NULL -> Wq/s_w are inputs. */
+halo_status halo_linear_fwd(const halo_linear_desc* desc, const void* X, const void* W, void* Y,
+                            int8_t* Xq, float* s_x, int8_t* Wq, float* s_w, void* workspace,
+                            size_t workspace_bytes, void* stream);
+
+/* Backward.  E bf16 [b x n] (ld n); EX [b x m] and G [n x m] in desc->out_dt; either may be NULL to
+ * skip that product (not both). */
+halo_status halo_linear_bwd(const halo_linear_desc* desc, const void* E, const int8_t* Xq,
+                            const float* s_x, const int8_t* Wq, const float* s_w, void* EX, void* G,
+                            void* workspace, size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HALO_H */

@@ -1,0 +1,248 @@
+"""Thin ctypes binding of libhalo's C ABI (include/halo.h).
+
+Argument marshalling only: every step of the HALO linear layer runs in the HIP kernels of libhalo.so.
+torch is used for device memory and the current stream, nothing else.  There is no CPU fallback: if the
+shared library is missing, importing a function from here raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import Optional, Tuple
+
+import torch
+
+from . import _build
+
+HALO_OK = 0
+HALO_EINVAL, HALO_ESHAPE, HALO_EALIGN, HALO_EWORKSPACE, HALO_EUNSUPPORTED, HALO_EHIP = 1, 2, 3, 4, 5, 6
+HALO_BF16, HALO_F32 = 0, 1
+HALO_QUANT_ROWS, HALO_QUANT_COLS_T = 0, 1
+
+EXPORTED_SYMBOLS = (
+    "halo_status_string", "halo_version",
+    "halo_hadamard_quant_workspace_bytes", "halo_hadamard_quant",
+    "halo_gemm_i8",
+    "halo_dequant_unrotate_workspace_bytes", "halo_dequant_unrotate",
+    "halo_linear_workspace_bytes", "halo_linear_fwd", "halo_linear_bwd",
+)
+
+
+class HaloError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__("%s failed: %s (status %d)" % (where, status_string(status), status))
+
+
+class LinearDesc(ctypes.Structure):
+    _fields_ = [("b", ctypes.c_int64), ("m", ctypes.c_int64), ("n", ctypes.c_int64),
+                ("level", ctypes.c_int32), ("had_block_m", ctypes.c_int32),
+                ("had_block_b", ctypes.c_int32), ("out_dt", ctypes.c_int32)]
+
+
+_lib: Optional[ctypes.CDLL] = None
+
+
+def load_library(path: Optional[str] = None) -> ctypes.CDLL:
+    """Load libhalo.so (built in-tree by _build.build()).  Raises if it is not there."""
+    global _lib
+    if _lib is not None and path is None:
+        return _lib
+    path = path or _build.LIB_PATH
+    if not os.path.exists(path):
+        raise RuntimeError(
+            "libhalo.so is not built (%s). Run `python -c 'import __graft_entry__ as g; g.build()'`; "
+            "there is no fallback path." % path)
+    lib = ctypes.CDLL(path)
+    c = ctypes
+    vp, i64, i32, sz = c.c_void_p, c.c_int64, c.c_int32, c.c_size_t
+    lib.halo_status_string.restype = c.c_char_p
+    lib.halo_status_string.argtypes = [c.c_int]
+    lib.halo_version.restype = c.c_int
+    lib.halo_version.argtypes = []
+    lib.halo_hadamard_quant_workspace_bytes.restype = sz
+    lib.halo_hadamard_quant_workspace_bytes.argtypes = [i64, i64, c.c_int, i32]
+    lib.halo_hadamard_quant.restype = c.c_int
+    lib.halo_hadamard_quant.argtypes = [vp, c.c_int, i64, i64, i64, c.c_int, i32, i32, vp, vp, i64, vp, vp, sz, vp]
+    lib.halo_gemm_i8.restype = c.c_int
+    lib.halo_gemm_i8.argtypes = [vp, i64, vp, i64, c.c_int, i64, i64, i64, vp, vp, vp, c.c_int, i64, vp, i64, vp]
+    lib.halo_dequant_unrotate_workspace_bytes.restype = sz
+    lib.halo_dequant_unrotate_workspace_bytes.argtypes = [i64, i64, i32]
+    lib.halo_dequant_unrotate.restype = c.c_int
+    lib.halo_dequant_unrotate.argtypes = [vp, i64, i64, i64, vp, i32, i32, vp, c.c_int, i64, vp, sz, vp]
+    lib.halo_linear_workspace_bytes.restype = sz
+    lib.halo_linear_workspace_bytes.argtypes = [c.POINTER(LinearDesc)]
+    lib.halo_linear_fwd.restype = c.c_int
+    lib.halo_linear_fwd.argtypes = [c.POINTER(LinearDesc), vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.halo_linear_bwd.restype = c.c_int
+    lib.halo_linear_bwd.argtypes = [c.POINTER(LinearDesc), vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    if path == _build.LIB_PATH:
+        _lib = lib
+    return lib
+
+
+def status_string(status: int) -> str:
+    return load_library().halo_status_string(int(status)).decode()
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dt(dtype: torch.dtype) -> int:
+    if dtype == torch.bfloat16:
+        return HALO_BF16
+    if dtype == torch.float32:
+        return HALO_F32
+    raise TypeError("HALO tensors are bf16 or fp32, got %s" % dtype)
+
+
+def _check(status: int, where: str):
+    if status != HALO_OK:
+        raise HaloError(status, where)
+
+
+def _need_cuda(*ts):
+    for t in ts:
+        if t is not None and not t.is_cuda:
+            raise ValueError("libhalo takes device tensors only")
+
+
+# ------------------------------------------------------------------------------------------------ entry points
+def halo_hadamard_quant(x: torch.Tensor, *, axis: int = HALO_QUANT_ROWS, had_block: int = 0,
+                        had_block_left: int = 0, fold: Optional[torch.Tensor] = None,
+                        out_q: Optional[torch.Tensor] = None, out_scale: Optional[torch.Tensor] = None,
+                        workspace: Optional[torch.Tensor] = None) -> Tuple[torch.Tensor, torch.Tensor]:
+    """rotate -> fold -> absmax -> INT8.  Returns (codes int8, scales fp32)."""
+    lib = load_library()
+    _need_cuda(x, fold, out_q, out_scale, workspace)
+    assert x.dim() == 2 and x.stride(1) == 1
+    rows, cols = x.shape
+    if axis == HALO_QUANT_ROWS:
+        qshape, nscale = (rows, cols), rows
+    else:
+        qshape, nscale = (cols, rows), cols
+    if out_q is None:
+        out_q = torch.empty(qshape, dtype=torch.int8, device=x.device)
+    if out_scale is None:
+        out_scale = torch.empty((nscale,), dtype=torch.float32, device=x.device)
+    need = lib.halo_hadamard_quant_workspace_bytes(rows, cols, axis, had_block_left)
+    if workspace is None and need:
+        workspace = torch.empty((need,), dtype=torch.uint8, device=x.device)
+    st = lib.halo_hadamard_quant(_ptr(x), _dt(x.dtype), rows, cols, x.stride(0) if rows else cols, axis,
+                                 had_block, had_block_left, _ptr(fold), _ptr(out_q),
+                                 out_q.stride(0) if out_q.numel() else qshape[1], _ptr(out_scale), _ptr(workspace),
+                                 workspace.numel() if workspace is not None else 0, _stream())
+    _check(st, "halo_hadamard_quant")
+    return out_q, out_scale
+
+
+def halo_gemm_i8(a: torch.Tensor, b: torch.Tensor, *, trans_b: bool, row_scale: Optional[torch.Tensor] = None,
+                 col_scale: Optional[torch.Tensor] = None, out_dtype: Optional[torch.dtype] = torch.float32,
+                 want_acc: bool = False, out: Optional[torch.Tensor] = None,
+                 acc_out: Optional[torch.Tensor] = None):
+    """C = diag(row_scale) (A op(B)) diag(col_scale); returns (C or None, acc or None)."""
+    lib = load_library()
+    _need_cuda(a, b, row_scale, col_scale, out, acc_out)
+    assert a.dtype == torch.int8 and b.dtype == torch.int8 and a.dim() == 2 and b.dim() == 2
+    M, K = a.shape
+    N = b.shape[0] if trans_b else b.shape[1]
+    assert (b.shape[1] if trans_b else b.shape[0]) == K
+    if out is None and out_dtype is not None:
+        out = torch.empty((M, N), dtype=out_dtype, device=a.device)
+    if acc_out is None and want_acc:
+        acc_out = torch.empty((M, N), dtype=torch.int32, device=a.device)
+    st = lib.halo_gemm_i8(_ptr(a), a.stride(0) if M else K, _ptr(b), b.stride(0) if b.shape[0] else b.shape[1],
+                          1 if trans_b else 0, M, N, K, _ptr(row_scale), _ptr(col_scale), _ptr(out),
+                          _dt(out.dtype) if out is not None else HALO_F32,
+                          (out.stride(0) if M else N) if out is not None else 0, _ptr(acc_out),
+                          (acc_out.stride(0) if M else N) if acc_out is not None else 0, _stream())
+    _check(st, "halo_gemm_i8")
+    return out, acc_out
+
+
+def halo_dequant_unrotate(acc: torch.Tensor, row_scale: Optional[torch.Tensor], *, had_block: int = 0,
+                          had_block_left: int = 0, out_dtype: torch.dtype = torch.float32,
+                          out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    lib = load_library()
+    _need_cuda(acc, row_scale, out, workspace)
+    assert acc.dtype == torch.int32 and acc.dim() == 2
+    rows, cols = acc.shape
+    if out is None:
+        out = torch.empty((rows, cols), dtype=out_dtype, device=acc.device)
+    need = lib.halo_dequant_unrotate_workspace_bytes(rows, cols, had_block_left)
+    if workspace is None and need:
+        workspace = torch.empty((need,), dtype=torch.uint8, device=acc.device)
+    st = lib.halo_dequant_unrotate(_ptr(acc), acc.stride(0) if rows else cols, rows, cols, _ptr(row_scale), had_block,
+                                   had_block_left, _ptr(out), _dt(out.dtype), out.stride(0) if rows else cols,
+                                   _ptr(workspace), workspace.numel() if workspace is not None else 0, _stream())
+    _check(st, "halo_dequant_unrotate")
+    return out
+
+
+@dataclass
+class LinearState:
+    """What the layer keeps between forward and backward (Section 3.2, Step 2): codes and scales only."""
+    Xq: torch.Tensor
+    s_x: torch.Tensor
+    Wq: torch.Tensor
+    s_w: torch.Tensor
+
+
+def make_desc(b: int, m: int, n: int, level: int, out_dtype: torch.dtype = torch.bfloat16,
+              had_block_m: int = 0, had_block_b: int = 0) -> LinearDesc:
+    return LinearDesc(b, m, n, level, had_block_m, had_block_b, _dt(out_dtype))
+
+
+def halo_linear_workspace_bytes(desc: LinearDesc) -> int:
+    return int(load_library().halo_linear_workspace_bytes(ctypes.byref(desc)))
+
+
+def halo_linear_fwd(desc: LinearDesc, X: Optional[torch.Tensor], W: Optional[torch.Tensor], *,
+                    state: Optional[LinearState] = None, Y: Optional[torch.Tensor] = None):
+    """Forward product; returns (Y, LinearState).  Pass X=None / W=None with a `state` that already holds
+    the corresponding codes to reuse them."""
+    lib = load_library()
+    dev = (X if X is not None else state.Xq).device
+    odt = torch.bfloat16 if desc.out_dt == HALO_BF16 else torch.float32
+    if state is None:
+        state = LinearState(torch.empty((desc.b, desc.m), dtype=torch.int8, device=dev),
+                            torch.empty((desc.b,), dtype=torch.float32, device=dev),
+                            torch.empty((desc.n, desc.m), dtype=torch.int8, device=dev),
+                            torch.empty((desc.n,), dtype=torch.float32, device=dev))
+    if Y is None:
+        Y = torch.empty((desc.b, desc.n), dtype=odt, device=dev)
+    _need_cuda(X, W, Y, state.Xq, state.Wq)
+    for t in (X, W):
+        assert t is None or (t.dtype == torch.bfloat16 and t.is_contiguous())
+    st = lib.halo_linear_fwd(ctypes.byref(desc), _ptr(X), _ptr(W), _ptr(Y), _ptr(state.Xq), _ptr(state.s_x),
+                             _ptr(state.Wq), _ptr(state.s_w), None, 0, _stream())
+    _check(st, "halo_linear_fwd")
+    return Y, state
+
+
+def halo_linear_bwd(desc: LinearDesc, E: torch.Tensor, state: LinearState, *, want_ex: bool = True,
+                    want_g: bool = True, workspace: Optional[torch.Tensor] = None,
+                    EX: Optional[torch.Tensor] = None, G: Optional[torch.Tensor] = None):
+    """Both backward products; returns (E_X or None, G or None)."""
+    lib = load_library()
+    _need_cuda(E, workspace, EX, G)
+    assert E.dtype == torch.bfloat16 and E.is_contiguous()
+    odt = torch.bfloat16 if desc.out_dt == HALO_BF16 else torch.float32
+    if want_ex and EX is None:
+        EX = torch.empty((desc.b, desc.m), dtype=odt, device=E.device)
+    if want_g and G is None:
+        G = torch.empty((desc.n, desc.m), dtype=odt, device=E.device)
+    need = halo_linear_workspace_bytes(desc)
+    if workspace is None:
+        workspace = torch.empty((max(need, 1),), dtype=torch.uint8, device=E.device)
+    st = lib.halo_linear_bwd(ctypes.byref(desc), _ptr(E), _ptr(state.Xq), _ptr(state.s_x), _ptr(state.Wq),
+                             _ptr(state.s_w), _ptr(EX) if want_ex else None, _ptr(G) if want_g else None,
+                             _ptr(workspace), workspace.numel(), _stream())
+    _check(st, "halo_linear_bwd")
+    return (EX if want_ex else None), (G if want_g else None)

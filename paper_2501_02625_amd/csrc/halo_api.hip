@@ -1,0 +1,315 @@
+// C ABI of libhalo: argument checking on the host, then kernel launches on the caller's stream.
+#include <cmath>
+#include <cstdint>
+
+#include "halo_internal.h"
+
+using namespace halo;
+
+namespace {
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline size_t round256(size_t v) { return (v + 255) & ~size_t(255); }
+inline halo_status from_hip(hipError_t e) { return e == hipSuccess ? HALO_OK : HALO_EHIP; }
+
+// Hadamard block check: 0, or a power of two in [2, cap] dividing `len`.
+inline halo_status check_block(int32_t block, int64_t len, int64_t cap) {
+    if (block < 0) return HALO_EINVAL;
+    if (block == 0) return HALO_OK;
+    if (block == 1 || !is_pow2(block)) return HALO_ESHAPE;
+    if (block > cap) return HALO_EUNSUPPORTED;
+    if (len % block != 0) return HALO_ESHAPE;
+    return HALO_OK;
+}
+
+constexpr int64_t kMaxRightBlock = 4096;
+constexpr int64_t kMaxLeftBlock = 65536;
+constexpr int64_t kMaxDim = int64_t(1) << 22;   // rows / columns of any matrix argument
+
+struct BwdWorkspace {
+    size_t eq, s_e, eqt, s_g, amax, acc, f32, total;
+};
+
+inline int32_t default_block(int64_t len, int64_t cap) {
+    int64_t b = len & -len;
+    if (b > cap) b = cap;
+    return b >= 2 ? (int32_t)b : 0;
+}
+
+halo_status resolve_desc(const halo_linear_desc* d, int32_t* hm, int32_t* hb) {
+    if (!d) return HALO_EINVAL;
+    if (d->b < 0 || d->m < 0 || d->n < 0) return HALO_EINVAL;
+    if (d->level < 0 || d->level > 2) return HALO_EINVAL;
+    if (d->out_dt != HALO_BF16 && d->out_dt != HALO_F32) return HALO_EINVAL;
+    if (d->b > kMaxDim || d->m > kMaxDim || d->n > kMaxDim) return HALO_EUNSUPPORTED;
+    if (d->b % 16 || d->m % 16 || d->n % 16) return HALO_ESHAPE;
+    if (d->m > kMaxRowCols || d->n > kMaxRowCols) return HALO_EUNSUPPORTED;
+    *hm = 0;
+    *hb = 0;
+    if (d->level >= 1) {
+        *hm = d->had_block_m ? d->had_block_m : default_block(d->m, kMaxRightBlock);
+        halo_status st = check_block(*hm, d->m, kMaxRightBlock);
+        if (st != HALO_OK) return st;
+    }
+    if (d->level >= 2) {
+        *hb = d->had_block_b ? d->had_block_b : default_block(d->b, kMaxLeftBlock);
+        halo_status st = check_block(*hb, d->b, kMaxLeftBlock);
+        if (st != HALO_OK) return st;
+    }
+    return HALO_OK;
+}
+
+BwdWorkspace bwd_layout(const halo_linear_desc* d) {
+    BwdWorkspace w{};
+    size_t off = 0;
+    const size_t b = (size_t)d->b, m = (size_t)d->m, n = (size_t)d->n;
+    w.eq = off;   off += round256(b * n);
+    w.s_e = off;  off += round256(b * 4);
+    w.eqt = off;  off += round256(n * b);
+    w.s_g = off;  off += round256(n * 4);
+    w.amax = off; off += round256(n * 4);
+    w.acc = off;  off += round256((b > n ? b : n) * m * 4);
+    w.f32 = off;
+    if (d->level >= 2) off += round256(b * (m > n ? m : n) * 4);
+    w.total = off;
+    return w;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* halo_status_string(halo_status s) {
+    switch (s) {
+        case HALO_OK: return "ok";
+        case HALO_EINVAL: return "invalid argument";
+        case HALO_ESHAPE: return "sizes do not fit together";
+        case HALO_EALIGN: return "pointer or leading dimension not 16-byte aligned";
+        case HALO_EWORKSPACE: return "workspace missing or too small";
+        case HALO_EUNSUPPORTED: return "not supported by this build";
+        case HALO_EHIP: return "HIP call failed";
+    }
+    return "unknown status";
+}
+
+int halo_version(void) { return 1; }
+
+// ------------------------------------------------------------------------------------------------
+size_t halo_hadamard_quant_workspace_bytes(int64_t rows, int64_t cols, halo_axis axis, int32_t had_block_left) {
+    if (rows <= 0 || cols <= 0) return 0;
+    if (axis == HALO_QUANT_COLS_T) return round256((size_t)cols * 4);
+    if (had_block_left > 0) return round256((size_t)rows * (size_t)cols * 4);
+    return 0;
+}
+
+halo_status halo_hadamard_quant(const void* in, halo_dtype in_dt, int64_t rows, int64_t cols, int64_t ld_in,
+                                halo_axis axis, int32_t had_block, int32_t had_block_left, const float* fold,
+                                int8_t* out_q, int64_t ld_q, float* out_scale, void* workspace,
+                                size_t workspace_bytes, void* stream) {
+    if (rows < 0 || cols < 0) return HALO_EINVAL;
+    if (in_dt != HALO_BF16 && in_dt != HALO_F32) return HALO_EINVAL;
+    if (axis != HALO_QUANT_ROWS && axis != HALO_QUANT_COLS_T) return HALO_EINVAL;
+    if (rows == 0 || cols == 0) return HALO_OK;
+    if (!in || !out_q || !out_scale) return HALO_EINVAL;
+    if (rows > kMaxDim || cols > kMaxDim) return HALO_EUNSUPPORTED;
+    const int64_t esz = in_dt == HALO_BF16 ? 2 : 4;
+    if (ld_in < cols) return HALO_ESHAPE;
+    if (ld_q < (axis == HALO_QUANT_ROWS ? cols : rows)) return HALO_ESHAPE;
+    if (!aligned16(in) || !aligned16(out_q) || (ld_in * esz) % 16 || ld_q % 16) return HALO_EALIGN;
+    if (fold && !aligned16(fold)) return HALO_EALIGN;
+    halo_status st = check_block(had_block, cols, kMaxRightBlock);
+    if (st != HALO_OK) return st;
+    st = check_block(had_block_left, rows, kMaxLeftBlock);
+    if (st != HALO_OK) return st;
+    const size_t need = halo_hadamard_quant_workspace_bytes(rows, cols, axis, had_block_left);
+    if (need > 0 && (!workspace || workspace_bytes < need)) return HALO_EWORKSPACE;
+    if (need > 0 && !aligned16(workspace)) return HALO_EALIGN;
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+
+    if (axis == HALO_QUANT_COLS_T) {
+        if (had_block || had_block_left) return HALO_EUNSUPPORTED;
+        if (in_dt != HALO_BF16) return HALO_EUNSUPPORTED;
+        ColQuantArgs a{in, ld_in, rows, cols, fold, out_q, ld_q, out_scale, reinterpret_cast<float*>(workspace)};
+        return from_hip(launch_col_quant_t(a, s));
+    }
+    if (cols > kMaxRowCols) return HALO_EUNSUPPORTED;
+    RowArgs r{};
+    r.rows = rows; r.cols = cols; r.fold = fold; r.out = out_q; r.ld_out = ld_q; r.out_scale = out_scale;
+    r.log_block = had_block ? ilog2_exact(had_block) : 0;
+    if (had_block_left == 0) {
+        r.in = in; r.ld_in = ld_in;
+        return from_hip(launch_row_transform(r, in_dt == HALO_BF16 ? IN_BF16 : IN_F32, OUT_Q8, s));
+    }
+    // left-hand rotation first (strided passes into fp32 scratch), then the row kernel on the scratch
+    if ((cols * 4) % 16) return HALO_EALIGN;   // scratch rows must stay 16-byte aligned
+    float* tmp = reinterpret_cast<float*>(workspace);
+    ColFwhtArgs c{in, in_dt == HALO_BF16 ? IN_BF16 : IN_F32, ld_in, tmp, OUT_F32, cols, tmp, cols, rows, cols,
+                  ilog2_exact(had_block_left)};
+    hipError_t e = launch_col_fwht(c, s);
+    if (e != hipSuccess) return HALO_EHIP;
+    r.in = tmp; r.ld_in = cols;
+    return from_hip(launch_row_transform(r, IN_F32, OUT_Q8, s));
+}
+
+// ------------------------------------------------------------------------------------------------
+halo_status halo_gemm_i8(const int8_t* A, int64_t lda, const int8_t* B, int64_t ldb, int transB, int64_t M,
+                         int64_t N, int64_t K, const float* row_scale, const float* col_scale, void* C,
+                         halo_dtype c_dt, int64_t ldc, int32_t* acc_out, int64_t ld_acc, void* stream) {
+    if (M < 0 || N < 0 || K < 0) return HALO_EINVAL;
+    if (c_dt != HALO_BF16 && c_dt != HALO_F32) return HALO_EINVAL;
+    if (M == 0 || N == 0) return HALO_OK;
+    if (!C && !acc_out) return HALO_EINVAL;
+    if (K > 0 && (!A || !B)) return HALO_EINVAL;
+    if (M > kMaxDim || N > kMaxDim || K > kMaxDim) return HALO_EUNSUPPORTED;
+    if (K % 16) return HALO_ESHAPE;
+    if (127ll * 127ll * K >= (1ll << 31)) return HALO_ESHAPE;
+    if (K > 0) {
+        if (lda < K || ldb < (transB ? K : N)) return HALO_ESHAPE;
+        if (!aligned16(A) || !aligned16(B) || lda % 16 || ldb % 16) return HALO_EALIGN;
+    }
+    if (C) {
+        if (ldc < N) return HALO_ESHAPE;
+        if (!aligned16(C) || (ldc * (c_dt == HALO_BF16 ? 2 : 4)) % 16) return HALO_EALIGN;
+    }
+    if (acc_out) {
+        if (ld_acc < N) return HALO_ESHAPE;
+        if (!aligned16(acc_out) || (ld_acc * 4) % 16) return HALO_EALIGN;
+    }
+    GemmArgs g{A, lda, B, ldb, transB ? 1 : 0, M, N, K, row_scale, col_scale, C, c_dt == HALO_F32 ? 1 : 0, ldc,
+               acc_out, ld_acc};
+    return from_hip(launch_gemm_i8(g, reinterpret_cast<hipStream_t>(stream)));
+}
+
+// ------------------------------------------------------------------------------------------------
+size_t halo_dequant_unrotate_workspace_bytes(int64_t rows, int64_t cols, int32_t had_block_left) {
+    if (rows <= 0 || cols <= 0 || had_block_left <= 0) return 0;
+    return round256((size_t)rows * (size_t)cols * 4);
+}
+
+halo_status halo_dequant_unrotate(const int32_t* acc, int64_t ld_acc, int64_t rows, int64_t cols,
+                                  const float* row_scale, int32_t had_block, int32_t had_block_left, void* out,
+                                  halo_dtype out_dt, int64_t ld_out, void* workspace, size_t workspace_bytes,
+                                  void* stream) {
+    if (rows < 0 || cols < 0) return HALO_EINVAL;
+    if (out_dt != HALO_BF16 && out_dt != HALO_F32) return HALO_EINVAL;
+    if (rows == 0 || cols == 0) return HALO_OK;
+    if (!acc || !out) return HALO_EINVAL;
+    if (rows > kMaxDim || cols > kMaxRowCols) return HALO_EUNSUPPORTED;
+    if (ld_acc < cols || ld_out < cols) return HALO_ESHAPE;
+    if (!aligned16(acc) || !aligned16(out) || (ld_acc * 4) % 16 || (ld_out * (out_dt == HALO_BF16 ? 2 : 4)) % 16)
+        return HALO_EALIGN;
+    halo_status st = check_block(had_block, cols, kMaxRightBlock);
+    if (st != HALO_OK) return st;
+    st = check_block(had_block_left, rows, kMaxLeftBlock);
+    if (st != HALO_OK) return st;
+    const size_t need = halo_dequant_unrotate_workspace_bytes(rows, cols, had_block_left);
+    if (need > 0 && (!workspace || workspace_bytes < need)) return HALO_EWORKSPACE;
+    if (need > 0 && (!aligned16(workspace) || (cols * 4) % 16)) return HALO_EALIGN;
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+
+    RowArgs r{};
+    r.in = acc; r.ld_in = ld_acc; r.rows = rows; r.cols = cols; r.pre_scale = row_scale;
+    r.log_block = had_block ? ilog2_exact(had_block) : 0;
+    if (had_block_left == 0) {
+        r.out = out; r.ld_out = ld_out;
+        return from_hip(launch_row_transform(r, IN_I32, out_dt == HALO_BF16 ? OUT_BF16 : OUT_F32, s));
+    }
+    float* tmp = reinterpret_cast<float*>(workspace);
+    r.out = tmp; r.ld_out = cols;
+    hipError_t e = launch_row_transform(r, IN_I32, OUT_F32, s);
+    if (e != hipSuccess) return HALO_EHIP;
+    ColFwhtArgs c{tmp, IN_F32, cols, out, out_dt == HALO_BF16 ? OUT_BF16 : OUT_F32, ld_out, tmp, cols, rows, cols,
+                  ilog2_exact(had_block_left)};
+    return from_hip(launch_col_fwht(c, s));
+}
+
+// ------------------------------------------------------------------------------------------------
+size_t halo_linear_workspace_bytes(const halo_linear_desc* desc) {
+    int32_t hm, hb;
+    if (resolve_desc(desc, &hm, &hb) != HALO_OK) return 0;
+    return bwd_layout(desc).total;
+}
+
+halo_status halo_linear_fwd(const halo_linear_desc* desc, const void* X, const void* W, void* Y, int8_t* Xq,
+                            float* s_x, int8_t* Wq, float* s_w, void* workspace, size_t workspace_bytes,
+                            void* stream) {
+    (void)workspace; (void)workspace_bytes;
+    int32_t hm, hb;
+    halo_status st = resolve_desc(desc, &hm, &hb);
+    if (st != HALO_OK) return st;
+    if (!Y || !Xq || !s_x || !Wq || !s_w) return HALO_EINVAL;
+    const int64_t b = desc->b, m = desc->m, n = desc->n;
+    if (b == 0 || n == 0) return HALO_OK;
+    if ((X && !aligned16(X)) || (W && !aligned16(W)) || !aligned16(Y) || !aligned16(Xq) || !aligned16(Wq))
+        return HALO_EALIGN;
+    const halo_dtype odt = (halo_dtype)desc->out_dt;
+    if (X) {
+        st = halo_hadamard_quant(X, HALO_BF16, b, m, m, HALO_QUANT_ROWS, hm, 0, nullptr, Xq, m, s_x, nullptr, 0, stream);
+        if (st != HALO_OK) return st;
+    }
+    if (W) {
+        st = halo_hadamard_quant(W, HALO_BF16, n, m, m, HALO_QUANT_ROWS, hm, 0, nullptr, Wq, m, s_w, nullptr, 0, stream);
+        if (st != HALO_OK) return st;
+    }
+    return halo_gemm_i8(Xq, m, Wq, m, 1, b, n, m, s_x, s_w, Y, odt, n, nullptr, 0, stream);
+}
+
+halo_status halo_linear_bwd(const halo_linear_desc* desc, const void* E, const int8_t* Xq, const float* s_x,
+                            const int8_t* Wq, const float* s_w, void* EX, void* G, void* workspace,
+                            size_t workspace_bytes, void* stream) {
+    int32_t hm, hb;
+    halo_status st = resolve_desc(desc, &hm, &hb);
+    if (st != HALO_OK) return st;
+    if (!E || (!EX && !G)) return HALO_EINVAL;
+    if (EX && (!Wq || !s_w)) return HALO_EINVAL;
+    if (G && (!Xq || !s_x)) return HALO_EINVAL;
+    const int64_t b = desc->b, m = desc->m, n = desc->n;
+    if (b == 0 || m == 0 || n == 0) return HALO_OK;
+    const BwdWorkspace L = bwd_layout(desc);
+    if (!workspace || workspace_bytes < L.total) return HALO_EWORKSPACE;
+    if (!aligned16(workspace) || !aligned16(E) || (EX && !aligned16(EX)) || (G && !aligned16(G))) return HALO_EALIGN;
+    const halo_dtype odt = (halo_dtype)desc->out_dt;
+    const int level = desc->level;
+    unsigned char* ws = reinterpret_cast<unsigned char*>(workspace);
+    int8_t* Eq = reinterpret_cast<int8_t*>(ws + L.eq);
+    float* s_e = reinterpret_cast<float*>(ws + L.s_e);
+    int8_t* EqT = reinterpret_cast<int8_t*>(ws + L.eqt);
+    float* s_g = reinterpret_cast<float*>(ws + L.s_g);
+    float* amax = reinterpret_cast<float*>(ws + L.amax);
+    int32_t* acc = reinterpret_cast<int32_t*>(ws + L.acc);
+    float* f32 = reinterpret_cast<float*>(ws + L.f32);
+
+    if (EX) {
+        // (E_Y)_Q or (H E_Y)_Q with the saved weight scales folded in
+        st = halo_hadamard_quant(E, HALO_BF16, b, n, n, HALO_QUANT_ROWS, 0, level >= 2 ? hb : 0, s_w, Eq, n, s_e, f32,
+                                 level >= 2 ? round256((size_t)b * n * 4) : 0, stream);
+        if (st != HALO_OK) return st;
+        if (level == 0) {
+            st = halo_gemm_i8(Eq, n, Wq, m, 0, b, m, n, s_e, nullptr, EX, odt, m, nullptr, 0, stream);
+            if (st != HALO_OK) return st;
+        } else {
+            st = halo_gemm_i8(Eq, n, Wq, m, 0, b, m, n, nullptr, nullptr, nullptr, odt, 0, acc, m, stream);
+            if (st != HALO_OK) return st;
+            st = halo_dequant_unrotate(acc, m, b, m, s_e, hm, level >= 2 ? hb : 0, EX, odt, m, f32,
+                                       level >= 2 ? round256((size_t)b * m * 4) : 0, stream);
+            if (st != HALO_OK) return st;
+        }
+    }
+    if (G) {
+        st = halo_hadamard_quant(E, HALO_BF16, b, n, n, HALO_QUANT_COLS_T, 0, 0, s_x, EqT, b, s_g, amax,
+                                 round256((size_t)n * 4), stream);
+        if (st != HALO_OK) return st;
+        if (level == 0) {
+            st = halo_gemm_i8(EqT, b, Xq, m, 0, n, m, b, s_g, nullptr, G, odt, m, nullptr, 0, stream);
+            if (st != HALO_OK) return st;
+        } else {
+            st = halo_gemm_i8(EqT, b, Xq, m, 0, n, m, b, nullptr, nullptr, nullptr, odt, 0, acc, m, stream);
+            if (st != HALO_OK) return st;
+            st = halo_dequant_unrotate(acc, m, n, m, s_g, hm, 0, G, odt, m, nullptr, 0, stream);
+            if (st != HALO_OK) return st;
+        }
+    }
+    return HALO_OK;
+}
+
+}  // extern "C"

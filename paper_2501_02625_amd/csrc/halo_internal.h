@@ -1,0 +1,85 @@
+// Internal declarations shared by the HIP translation units of libhalo (not part of the C ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "halo.h"
+
+namespace halo {
+
+enum InKind { IN_BF16 = 0, IN_F32 = 1, IN_I32 = 2 };
+enum OutKind { OUT_Q8 = 0, OUT_BF16 = 1, OUT_F32 = 2 };
+
+// ---- row transform: [pre-scale] -> right-hand FWHT -> [fold] -> {absmax+INT8 | bf16 | fp32} ----
+struct RowArgs {
+    const void* in;
+    int64_t ld_in;
+    int64_t rows, cols;
+    const float* pre_scale;  // IN_I32 only: per-row multiplier, may be null
+    const float* fold;       // per-column multiplier, may be null
+    void* out;
+    int64_t ld_out;
+    float* out_scale;        // OUT_Q8 only
+    int log_block;           // log2 of the Hadamard block, 0 = no rotation
+};
+// Largest row length the row kernels accept.
+constexpr int64_t kMaxRowCols = 32768;
+hipError_t launch_row_transform(const RowArgs& a, InKind in, OutKind out, hipStream_t s);
+
+// ---- left-hand (strided axis) FWHT: all stages of block 2^log_block, ascending, possibly several passes ----
+// in/out may alias when in_kind == out_kind == fp32.  tmp (fp32 [rows x ld_tmp]) is used when more than one
+// pass is needed and in/out cannot carry fp32 intermediates.
+struct ColFwhtArgs {
+    const void* in;
+    InKind in_kind;          // IN_BF16 or IN_F32
+    int64_t ld_in;
+    void* out;
+    OutKind out_kind;        // OUT_F32 or OUT_BF16
+    int64_t ld_out;
+    float* tmp;
+    int64_t ld_tmp;
+    int64_t rows, cols;
+    int log_block;
+};
+hipError_t launch_col_fwht(const ColFwhtArgs& a, hipStream_t s);
+
+// ---- column-wise absmax quantiser with transposed output (E^T)_Q ----
+struct ColQuantArgs {
+    const void* in;          // bf16 [rows x cols]
+    int64_t ld_in;
+    int64_t rows, cols;
+    const float* fold;       // per-row multiplier, may be null
+    int8_t* out_q;           // [cols x rows]
+    int64_t ld_q;
+    float* out_scale;        // [cols]
+    float* amax_ws;          // [cols] scratch: column absmax accumulated as bit patterns
+};
+hipError_t launch_col_quant_t(const ColQuantArgs& a, hipStream_t s);
+
+// ---- INT8 GEMM ----
+struct GemmArgs {
+    const int8_t* A;
+    int64_t lda;
+    const int8_t* B;
+    int64_t ldb;
+    int transB;
+    int64_t M, N, K;
+    const float* row_scale;
+    const float* col_scale;
+    void* C;
+    int c_is_f32;
+    int64_t ldc;
+    int32_t* acc_out;
+    int64_t ld_acc;
+};
+hipError_t launch_gemm_i8(const GemmArgs& a, hipStream_t s);
+
+inline int ilog2_exact(int64_t v) {
+    int l = 0;
+    while ((int64_t(1) << l) < v) ++l;
+    return l;
+}
+inline bool is_pow2(int64_t v) { return v > 0 && (v & (v - 1)) == 0; }
+
+}  // namespace halo

@@ -1,0 +1,143 @@
+"""CPU-only checks of the C ABI: the library loads, exports every declared symbol, and rejects bad
+arguments on the host before anything is launched (no device needed for any call made here)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2501_02625_amd import _build, binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(_build.LIB_PATH):
+        _build.build()
+    return binding.load_library()
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "halo.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(halo_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_functions()
+    assert set(names) == set(binding.EXPORTED_SYMBOLS)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_version_and_status_strings(lib):
+    assert lib.halo_version() >= 1
+    seen = {binding.status_string(s) for s in range(7)}
+    assert len(seen) == 7 and "ok" in seen
+
+
+def _p(v):
+    return ctypes.c_void_p(v)
+
+
+def test_hadamard_quant_argument_errors(lib):
+    f = lib.halo_hadamard_quant
+    good = dict(rows=64, cols=512, ld=512)
+    A, Q, S = _p(0x1000), _p(0x2000), _p(0x3000)
+    # null pointers
+    assert f(None, 0, 64, 512, 512, 0, 512, 0, None, Q, 512, S, None, 0, None) == binding.HALO_EINVAL
+    # negative size, bad enums
+    assert f(A, 0, -1, 512, 512, 0, 0, 0, None, Q, 512, S, None, 0, None) == binding.HALO_EINVAL
+    assert f(A, 7, 64, 512, 512, 0, 0, 0, None, Q, 512, S, None, 0, None) == binding.HALO_EINVAL
+    assert f(A, 0, 64, 512, 512, 9, 0, 0, None, Q, 512, S, None, 0, None) == binding.HALO_EINVAL
+    # block not a power of two / does not divide / too large
+    assert f(A, 0, 64, 512, 512, 0, 48, 0, None, Q, 512, S, None, 0, None) == binding.HALO_ESHAPE
+    assert f(A, 0, 64, 768, 768, 0, 512, 0, None, Q, 768, S, None, 0, None) == binding.HALO_ESHAPE
+    assert f(A, 0, 64, 8192, 8192, 0, 8192, 0, None, Q, 8192, S, None, 0, None) == binding.HALO_EUNSUPPORTED
+    # leading dimension too small, misaligned pointer / ld
+    assert f(A, 0, 64, 512, 256, 0, 0, 0, None, Q, 512, S, None, 0, None) == binding.HALO_ESHAPE
+    assert f(_p(0x1004), 0, 64, 512, 512, 0, 0, 0, None, Q, 512, S, None, 0, None) == binding.HALO_EALIGN
+    assert f(A, 0, 64, 500, 500, 0, 0, 0, None, Q, 512, S, None, 0, None) == binding.HALO_EALIGN
+    # left-hand rotation without workspace
+    assert f(A, 0, 64, 512, 512, 0, 0, 64, None, Q, 512, S, None, 0, None) == binding.HALO_EWORKSPACE
+    need = lib.halo_hadamard_quant_workspace_bytes(64, 512, 0, 64)
+    assert need >= 64 * 512 * 4
+    assert f(A, 0, 64, 512, 512, 0, 0, 64, None, Q, 512, S, _p(0x4000), need - 1, None) == binding.HALO_EWORKSPACE
+    # transposed-output axis has no rotation
+    need = lib.halo_hadamard_quant_workspace_bytes(64, 512, 1, 0)
+    assert f(A, 0, 64, 512, 512, 1, 512, 0, None, Q, 64, S, _p(0x4000), need, None) == binding.HALO_EUNSUPPORTED
+    # empty input is a no-op
+    assert f(None, 0, 0, 512, 512, 0, 0, 0, None, None, 512, None, None, 0, None) == binding.HALO_OK
+    assert good
+
+
+def test_gemm_argument_errors(lib):
+    f = lib.halo_gemm_i8
+    A, B, C = _p(0x1000), _p(0x2000), _p(0x3000)
+    assert f(A, 64, B, 64, 1, 32, 32, 64, None, None, None, 1, 32, None, 0, None) == binding.HALO_EINVAL
+    assert f(None, 64, B, 64, 1, 32, 32, 64, None, None, C, 1, 32, None, 0, None) == binding.HALO_EINVAL
+    assert f(A, 64, B, 64, 1, 32, 32, 40, None, None, C, 1, 32, None, 0, None) == binding.HALO_ESHAPE     # K % 16
+    assert f(A, 32, B, 64, 1, 32, 32, 64, None, None, C, 1, 32, None, 0, None) == binding.HALO_ESHAPE     # lda < K
+    assert f(A, 64, B, 16, 0, 32, 32, 64, None, None, C, 1, 32, None, 0, None) == binding.HALO_ESHAPE     # ldb < N
+    assert f(A, 72, B, 64, 1, 32, 32, 64, None, None, C, 1, 32, None, 0, None) == binding.HALO_EALIGN
+    assert f(A, 64, B, 64, 1, 32, 32, 64, None, None, C, 0, 36, None, 0, None) == binding.HALO_EALIGN     # bf16 ldc
+    assert f(A, 64, B, 64, 1, 32, 32, 64, None, None, C, 5, 32, None, 0, None) == binding.HALO_EINVAL
+    k_too_long = 1 << 18   # 127*127*K would overflow int32
+    assert f(A, k_too_long, B, k_too_long, 1, 32, 32, k_too_long, None, None, C, 1, 32, None, 0, None) == binding.HALO_ESHAPE
+    assert f(None, 0, None, 0, 1, 0, 32, 64, None, None, None, 1, 32, None, 0, None) == binding.HALO_OK
+
+
+def test_linear_desc_errors_and_workspace(lib):
+    d = binding.make_desc(2048, 4096, 4096, 1)
+    ws1 = binding.halo_linear_workspace_bytes(d)
+    assert ws1 >= 2048 * 4096 * 2 + 4096 * 4096 * 4
+    d2 = binding.make_desc(2048, 4096, 4096, 2)
+    assert binding.halo_linear_workspace_bytes(d2) >= ws1 + 2048 * 4096 * 4
+    P = _p(0x1000)
+    bad_level = binding.make_desc(64, 64, 64, 3)
+    assert lib.halo_linear_fwd(ctypes.byref(bad_level), P, P, P, P, P, P, P, None, 0, None) == binding.HALO_EINVAL
+    odd = binding.make_desc(60, 64, 64, 1)
+    assert lib.halo_linear_fwd(ctypes.byref(odd), P, P, P, P, P, P, P, None, 0, None) == binding.HALO_ESHAPE
+    blk = binding.make_desc(64, 96, 64, 1, had_block_m=64)
+    assert lib.halo_linear_fwd(ctypes.byref(blk), P, P, P, P, P, P, P, None, 0, None) == binding.HALO_ESHAPE
+    ok = binding.make_desc(64, 64, 64, 1)
+    assert lib.halo_linear_fwd(ctypes.byref(ok), P, P, None, P, P, P, P, None, 0, None) == binding.HALO_EINVAL
+    assert lib.halo_linear_bwd(ctypes.byref(ok), P, P, P, P, P, None, None, P, 1 << 30, None) == binding.HALO_EINVAL
+    assert lib.halo_linear_bwd(ctypes.byref(ok), P, P, P, P, P, P, P, P, 16, None) == binding.HALO_EWORKSPACE
+    assert lib.halo_linear_bwd(ctypes.byref(ok), P, P, P, P, P, P, P, None, 0, None) == binding.HALO_EWORKSPACE
+
+
+def test_dequant_unrotate_argument_errors(lib):
+    f = lib.halo_dequant_unrotate
+    A, O = _p(0x1000), _p(0x2000)
+    assert f(None, 64, 16, 64, None, 64, 0, O, 1, 64, None, 0, None) == binding.HALO_EINVAL
+    assert f(A, 64, 16, 64, None, 48, 0, O, 1, 64, None, 0, None) == binding.HALO_ESHAPE
+    assert f(A, 64, 16, 64, None, 64, 16, O, 1, 64, None, 0, None) == binding.HALO_EWORKSPACE
+    assert f(A, 32, 16, 64, None, 64, 0, O, 1, 64, None, 0, None) == binding.HALO_ESHAPE
+    assert f(A, 64, 16, 64, None, 64, 0, O, 0, 68, None, 0, None) == binding.HALO_EALIGN
+
+
+def test_binding_refuses_missing_library(tmp_path):
+    with pytest.raises(RuntimeError):
+        binding.load_library(str(tmp_path / "nope.so"))
+
+
+def test_inputs_are_deterministic_and_shaped():
+    import numpy as np
+    from paper_2501_02625_amd import inputs
+    cfg = inputs.CONFIGS["c1"]
+    a = inputs.make_linear_inputs(cfg)
+    b = inputs.make_linear_inputs(cfg)
+    assert a["X"].shape == (128, 512) and a["W"].shape == (512, 512) and "E" not in a
+    assert np.array_equal(a["X"], b["X"]) and np.array_equal(a["W"], b["W"])
+    X = inputs.bf16_bits_to_f32(a["X"])
+    cols = inputs.outlier_columns(512, 0.005, 0)
+    assert len(cols) == 3
+    rms = np.sqrt((X.astype(np.float64) ** 2).mean(axis=0))
+    assert np.all(rms[cols] > 25) and np.median(rms) < 1.5
+    assert abs(np.std(inputs.bf16_bits_to_f32(a["W"])) - 0.02) < 2e-3
+    E = inputs.bf16_bits_to_f32(inputs.make_errors(256, 64, 1))
+    assert np.max(np.abs(E)) > 8 * np.median(np.abs(E))     # heavy tails
+    assert inputs.CONFIGS["c2"].gemm_ops() == 6 * 2048 * 4096 * 4096
+    assert inputs.CONFIGS["c3"].had_block_m(14336) == 2048

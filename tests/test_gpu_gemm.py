@@ -1,0 +1,97 @@
+"""GPU parity: halo_gemm_i8 int32 accumulators bit-exact against the oracle's exact integer product."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import halo_oracle as orc
+from paper_2501_02625_amd import binding
+from tests import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+
+# M, N, K -- chosen to hit each macro-tile configuration, ragged edges and a K tail
+SHAPES = [
+    (128, 512, 512),       # config c1 forward
+    (32, 32, 16),
+    (1, 1, 64),
+    (300, 200, 272),       # ragged M, N; K not a multiple of the K step
+    (257, 129, 1040),
+    (2048, 4096, 256),     # 256x128 tiles
+    (4096, 4096, 128),     # 256x256 tiles
+    (4100, 3900, 80),      # 256x256 tiles with ragged edges
+    (512, 14336, 64),
+]
+
+
+def rand_codes(rng, shape, extreme=False):
+    if extreme:
+        return rng.choice(np.array([-127, 127], dtype=np.int8), size=shape)
+    return rng.integers(-127, 128, size=shape, dtype=np.int8)
+
+
+@pytest.mark.parametrize("M,N,K", SHAPES)
+@pytest.mark.parametrize("trans_b", [True, False])
+def test_gemm_accumulators_bit_exact(M, N, K, trans_b):
+    rng = np.random.default_rng(M * 7 + N * 3 + K)
+    a = rand_codes(rng, (M, K))
+    b = rand_codes(rng, (N, K) if trans_b else (K, N))
+    ldb = (b.shape[1] + 15) // 16 * 16
+    bd = torch.zeros((b.shape[0], ldb), dtype=torch.int8, device=gu.DEV)
+    bd[:, :b.shape[1]] = gu.to_dev(b)
+    _, acc = binding.halo_gemm_i8(gu.to_dev(a), bd[:, :b.shape[1]], trans_b=trans_b, out_dtype=None, want_acc=True,
+                                  acc_out=torch.full((M, (N + 3) // 4 * 4), -7, dtype=torch.int32, device=gu.DEV)[:, :N])
+    want = orc.gemm_codes(a, b.T if trans_b else b)
+    gu.assert_codes_equal(acc, want, "accumulators")
+
+
+@pytest.mark.parametrize("trans_b", [True, False])
+def test_gemm_extreme_codes_longest_k(trans_b):
+    """All +-127 at K = 14336: the largest magnitude the layer can produce, no int32 overflow."""
+    rng = np.random.default_rng(5)
+    M, N, K = 96, 160, 14336
+    a = rand_codes(rng, (M, K), extreme=True)
+    b = rand_codes(rng, (N, K) if trans_b else (K, N), extreme=True)
+    a[0] = 127
+    if trans_b:
+        b[0] = 127
+    else:
+        b[:, 0] = 127
+    _, acc = binding.halo_gemm_i8(gu.to_dev(a), gu.to_dev(b), trans_b=trans_b, out_dtype=None, want_acc=True)
+    want = orc.gemm_codes(a, b.T if trans_b else b)
+    assert want[0, 0] == 127 * 127 * K
+    gu.assert_codes_equal(acc, want, "accumulators")
+
+
+@pytest.mark.parametrize("odt", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("trans_b", [True, False])
+def test_gemm_scaled_epilogue(odt, trans_b):
+    rng = np.random.default_rng(6)
+    M, N, K = 200, 328, 512
+    a = rand_codes(rng, (M, K)); b = rand_codes(rng, (N, K) if trans_b else (K, N))
+    rs = (np.abs(rng.standard_normal(M)) * 1e-2 + 1e-4).astype(np.float32)
+    cs = (np.abs(rng.standard_normal(N)) * 1e-3 + 1e-5).astype(np.float32)
+    ldc = (N + 7) // 8 * 8
+    out = torch.zeros((M, ldc), dtype=odt, device=gu.DEV)
+    c, acc = binding.halo_gemm_i8(gu.to_dev(a), gu.to_dev(b), trans_b=trans_b, row_scale=gu.to_dev(rs),
+                                  col_scale=gu.to_dev(cs), out=out[:, :N], want_acc=True)
+    want_acc = orc.gemm_codes(a, b.T if trans_b else b)
+    want = orc.dequantize(want_acc, rs, cs)
+    gu.assert_codes_equal(acc, want_acc, "accumulators")
+    if odt == torch.float32:
+        gu.assert_f32_identical(c.contiguous(), want, "scaled output")
+    else:
+        gu.assert_bf16_within_one_ulp(c.contiguous(), want, "scaled bf16 output")
+    # row scale only / no scales
+    c2, _ = binding.halo_gemm_i8(gu.to_dev(a), gu.to_dev(b), trans_b=trans_b, row_scale=gu.to_dev(rs))
+    gu.assert_f32_identical(c2, orc.dequantize(want_acc, rs), "row-scaled output")
+
+
+def test_gemm_k_zero_writes_zeros_and_empty_is_noop():
+    a = torch.empty((8, 0), dtype=torch.int8, device=gu.DEV)
+    b = torch.empty((8, 0), dtype=torch.int8, device=gu.DEV)
+    c, acc = binding.halo_gemm_i8(a, b, trans_b=True, want_acc=True)
+    assert not c.any() and not acc.any()
+    a = torch.empty((0, 64), dtype=torch.int8, device=gu.DEV)
+    b = torch.empty((16, 64), dtype=torch.int8, device=gu.DEV)
+    c, _ = binding.halo_gemm_i8(a, b, trans_b=True)
+    assert c.shape == (0, 16)
