@@ -107,6 +107,13 @@ def _check(status: int, where: str):
         raise HaloError(status, where)
 
 
+def _empty_padded(rows: int, cols: int, dtype: torch.dtype, device) -> torch.Tensor:
+    """[rows, cols] view of a buffer whose row pitch is a multiple of 16 bytes (the ABI's alignment rule)."""
+    per16 = 16 // torch.empty((), dtype=dtype).element_size()
+    ld = (cols + per16 - 1) // per16 * per16
+    return torch.empty((rows, max(ld, per16)), dtype=dtype, device=device)[:, :cols]
+
+
 def _need_cuda(*ts):
     for t in ts:
         if t is not None and not t.is_cuda:
@@ -128,7 +135,7 @@ def halo_hadamard_quant(x: torch.Tensor, *, axis: int = HALO_QUANT_ROWS, had_blo
     else:
         qshape, nscale = (cols, rows), cols
     if out_q is None:
-        out_q = torch.empty(qshape, dtype=torch.int8, device=x.device)
+        out_q = _empty_padded(qshape[0], qshape[1], torch.int8, x.device)
     if out_scale is None:
         out_scale = torch.empty((nscale,), dtype=torch.float32, device=x.device)
     need = lib.halo_hadamard_quant_workspace_bytes(rows, cols, axis, had_block_left)
@@ -154,9 +161,9 @@ def halo_gemm_i8(a: torch.Tensor, b: torch.Tensor, *, trans_b: bool, row_scale: 
     N = b.shape[0] if trans_b else b.shape[1]
     assert (b.shape[1] if trans_b else b.shape[0]) == K
     if out is None and out_dtype is not None:
-        out = torch.empty((M, N), dtype=out_dtype, device=a.device)
+        out = _empty_padded(M, N, out_dtype, a.device)
     if acc_out is None and want_acc:
-        acc_out = torch.empty((M, N), dtype=torch.int32, device=a.device)
+        acc_out = _empty_padded(M, N, torch.int32, a.device)
     st = lib.halo_gemm_i8(_ptr(a), a.stride(0) if M else K, _ptr(b), b.stride(0) if b.shape[0] else b.shape[1],
                           1 if trans_b else 0, M, N, K, _ptr(row_scale), _ptr(col_scale), _ptr(out),
                           _dt(out.dtype) if out is not None else HALO_F32,
@@ -174,7 +181,7 @@ def halo_dequant_unrotate(acc: torch.Tensor, row_scale: Optional[torch.Tensor], 
     assert acc.dtype == torch.int32 and acc.dim() == 2
     rows, cols = acc.shape
     if out is None:
-        out = torch.empty((rows, cols), dtype=out_dtype, device=acc.device)
+        out = _empty_padded(rows, cols, out_dtype, acc.device)
     need = lib.halo_dequant_unrotate_workspace_bytes(rows, cols, had_block_left)
     if workspace is None and need:
         workspace = torch.empty((need,), dtype=torch.uint8, device=acc.device)

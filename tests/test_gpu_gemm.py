@@ -72,17 +72,21 @@ def test_gemm_scaled_epilogue(odt, trans_b):
     cs = (np.abs(rng.standard_normal(N)) * 1e-3 + 1e-5).astype(np.float32)
     ldc = (N + 7) // 8 * 8
     out = torch.zeros((M, ldc), dtype=odt, device=gu.DEV)
-    c, acc = binding.halo_gemm_i8(gu.to_dev(a), gu.to_dev(b), trans_b=trans_b, row_scale=gu.to_dev(rs),
+    ldb = (b.shape[1] + 15) // 16 * 16
+    bd = torch.zeros((b.shape[0], ldb), dtype=torch.int8, device=gu.DEV)
+    bd[:, :b.shape[1]] = gu.to_dev(b)
+    bd = bd[:, :b.shape[1]]
+    c, acc = binding.halo_gemm_i8(gu.to_dev(a), bd, trans_b=trans_b, row_scale=gu.to_dev(rs),
                                   col_scale=gu.to_dev(cs), out=out[:, :N], want_acc=True)
     want_acc = orc.gemm_codes(a, b.T if trans_b else b)
     want = orc.dequantize(want_acc, rs, cs)
     gu.assert_codes_equal(acc, want_acc, "accumulators")
     if odt == torch.float32:
-        gu.assert_f32_identical(c.contiguous(), want, "scaled output")
+        gu.assert_f32_identical(c, want, "scaled output")
     else:
-        gu.assert_bf16_within_one_ulp(c.contiguous(), want, "scaled bf16 output")
+        gu.assert_bf16_within_one_ulp(c, want, "scaled bf16 output")
     # row scale only / no scales
-    c2, _ = binding.halo_gemm_i8(gu.to_dev(a), gu.to_dev(b), trans_b=trans_b, row_scale=gu.to_dev(rs))
+    c2, _ = binding.halo_gemm_i8(gu.to_dev(a), bd, trans_b=trans_b, row_scale=gu.to_dev(rs))
     gu.assert_f32_identical(c2, orc.dequantize(want_acc, rs), "row-scaled output")
 
 
