@@ -112,6 +112,12 @@ halo_status halo_gemm_i8(const int8_t* A, int64_t lda, const int8_t* B, int64_t 
                          const float* col_scale, void* C, halo_dtype c_dt, int64_t ldc,
                          int32_t* acc_out, int64_t ld_acc, void* stream);
 
+/* Tuning hook for halo_gemm_i8 (process-wide, not thread-safe): config >= 0 forces one macro-tile /
+ * pipeline configuration for every following GEMM, -1 (the default) lets the library choose by shape.
+ * Configurations differ in speed only; results are identical.  Unknown values make halo_gemm_i8 return
+ * HALO_EHIP. */
+void halo_gemm_i8_set_config(int config);
+
 /* ---------------------------------------------------------------------------------------------
  * halo_dequant_unrotate: the tail of both backward products.   (Table "HALO levels": the trailing H^T
  * of  (E_Y)_Q (WH)_Q H^T  and  (E_Y^T)_Q (XH)_Q H^T,  and the leading H^T of level 2.)

@@ -23,7 +23,7 @@ HALO_QUANT_ROWS, HALO_QUANT_COLS_T = 0, 1
 EXPORTED_SYMBOLS = (
     "halo_status_string", "halo_version",
     "halo_hadamard_quant_workspace_bytes", "halo_hadamard_quant",
-    "halo_gemm_i8",
+    "halo_gemm_i8", "halo_gemm_i8_set_config",
     "halo_dequant_unrotate_workspace_bytes", "halo_dequant_unrotate",
     "halo_linear_workspace_bytes", "halo_linear_fwd", "halo_linear_bwd",
 )
@@ -67,6 +67,8 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.halo_hadamard_quant.argtypes = [vp, c.c_int, i64, i64, i64, c.c_int, i32, i32, vp, vp, i64, vp, vp, sz, vp]
     lib.halo_gemm_i8.restype = c.c_int
     lib.halo_gemm_i8.argtypes = [vp, i64, vp, i64, c.c_int, i64, i64, i64, vp, vp, vp, c.c_int, i64, vp, i64, vp]
+    lib.halo_gemm_i8_set_config.restype = None
+    lib.halo_gemm_i8_set_config.argtypes = [c.c_int]
     lib.halo_dequant_unrotate_workspace_bytes.restype = sz
     lib.halo_dequant_unrotate_workspace_bytes.argtypes = [i64, i64, i32]
     lib.halo_dequant_unrotate.restype = c.c_int
@@ -171,6 +173,11 @@ def halo_gemm_i8(a: torch.Tensor, b: torch.Tensor, *, trans_b: bool, row_scale: 
                           (acc_out.stride(0) if M else N) if acc_out is not None else 0, _stream())
     _check(st, "halo_gemm_i8")
     return out, acc_out
+
+
+def halo_gemm_i8_set_config(config: int) -> None:
+    """Force one GEMM tile configuration (-1 = automatic)."""
+    load_library().halo_gemm_i8_set_config(int(config))
 
 
 def halo_dequant_unrotate(acc: torch.Tensor, row_scale: Optional[torch.Tensor], *, had_block: int = 0,

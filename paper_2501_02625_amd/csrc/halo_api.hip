@@ -94,6 +94,8 @@ const char* halo_status_string(halo_status s) {
 
 int halo_version(void) { return 1; }
 
+void halo_gemm_i8_set_config(int config) { set_gemm_config(config); }
+
 // ------------------------------------------------------------------------------------------------
 size_t halo_hadamard_quant_workspace_bytes(int64_t rows, int64_t cols, halo_axis axis, int32_t had_block_left) {
     if (rows <= 0 || cols <= 0) return 0;

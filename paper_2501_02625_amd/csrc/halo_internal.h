@@ -74,6 +74,8 @@ struct GemmArgs {
     int64_t ld_acc;
 };
 hipError_t launch_gemm_i8(const GemmArgs& a, hipStream_t s);
+// Tuning hook: force one macro-tile configuration (-1 = choose by shape).
+void set_gemm_config(int cfg);
 
 inline int ilog2_exact(int64_t v) {
     int l = 0;

@@ -9,6 +9,16 @@ from tests import gpu_util as gu
 
 pytestmark = pytest.mark.gpu
 
+
+@pytest.fixture(autouse=True, scope="module")
+def forced_config():
+    """HALO_TEST_GEMM_CFG=<n> runs this module with one GEMM tile configuration forced (development aid)."""
+    import os
+    cfg = int(os.environ.get("HALO_TEST_GEMM_CFG", "-1"))
+    binding.halo_gemm_i8_set_config(cfg)
+    yield
+    binding.halo_gemm_i8_set_config(-1)
+
 # M, N, K -- chosen to hit each macro-tile configuration, ragged edges and a K tail
 SHAPES = [
     (128, 512, 512),       # config c1 forward
