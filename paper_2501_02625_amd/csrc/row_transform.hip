@@ -24,6 +24,12 @@
 namespace halo {
 namespace {
 
+// Build-time switch (both settings give identical bits): fold a power-of-two 1/sqrt(d) into the quantiser
+// scale instead of multiplying every element by it.
+#ifndef HALO_ROW_FOLD_C
+#define HALO_ROW_FOLD_C 0
+#endif
+
 constexpr float kRoundMagic = 12582912.0f;  // 1.5 * 2^23: adding it rounds |x| < 2^22 to an integer, ties to even
 
 template <int J>
@@ -74,13 +80,42 @@ __device__ __forceinline__ void stage_in_regs(float (&v)[VPL]) {
     }
 }
 
+// Eight  x <- x + s * partner(x)  steps in one asm block: v_fmac_f32 with the partner read through DPP.  The
+// leading s_nop supplies the two wait states a DPP read needs after a VALU write of the same register, whatever
+// the compiler placed before the block; inside the block every register is read and written by one instruction.
+#define HALO_FMAC_DPP8(CTRL)                                                                                   \
+    asm volatile("s_nop 1\n\t"                                                                                 \
+                 "v_fmac_f32_dpp %0, %0, %8 " CTRL " row_mask:0xf bank_mask:0xf\n\t"                            \
+                 "v_fmac_f32_dpp %1, %1, %8 " CTRL " row_mask:0xf bank_mask:0xf\n\t"                            \
+                 "v_fmac_f32_dpp %2, %2, %8 " CTRL " row_mask:0xf bank_mask:0xf\n\t"                            \
+                 "v_fmac_f32_dpp %3, %3, %8 " CTRL " row_mask:0xf bank_mask:0xf\n\t"                            \
+                 "v_fmac_f32_dpp %4, %4, %8 " CTRL " row_mask:0xf bank_mask:0xf\n\t"                            \
+                 "v_fmac_f32_dpp %5, %5, %8 " CTRL " row_mask:0xf bank_mask:0xf\n\t"                            \
+                 "v_fmac_f32_dpp %6, %6, %8 " CTRL " row_mask:0xf bank_mask:0xf\n\t"                            \
+                 "v_fmac_f32_dpp %7, %7, %8 " CTRL " row_mask:0xf bank_mask:0xf"                                 \
+                 : "+v"(v[r]), "+v"(v[r + 1]), "+v"(v[r + 2]), "+v"(v[r + 3]), "+v"(v[r + 4]), "+v"(v[r + 5]),   \
+                   "+v"(v[r + 6]), "+v"(v[r + 7])                                                               \
+                 : "v"(s))
+
 template <int VPL, int J>
 __device__ __forceinline__ void stage_across_lanes(float (&v)[VPL], int lane, int bperm_addr) {
+    static_assert(VPL % 8 == 0, "values per lane come in chunks of eight");
     const float s = ((lane >> J) & 1) ? -1.0f : 1.0f;
+    if constexpr (J == 0) {
 #pragma unroll
-    for (int r = 0; r < VPL; ++r) {
-        const float p = lane_xor<J>(v[r], bperm_addr);
-        v[r] = __builtin_fmaf(p, s, v[r]);
+        for (int r = 0; r < VPL; r += 8) HALO_FMAC_DPP8("quad_perm:[1,0,3,2]");
+    } else if constexpr (J == 1) {
+#pragma unroll
+        for (int r = 0; r < VPL; r += 8) HALO_FMAC_DPP8("quad_perm:[2,3,0,1]");
+    } else if constexpr (J == 3) {
+#pragma unroll
+        for (int r = 0; r < VPL; r += 8) HALO_FMAC_DPP8("row_ror:8");
+    } else {
+#pragma unroll
+        for (int r = 0; r < VPL; ++r) {
+            const float p = lane_xor<J>(v[r], bperm_addr);
+            v[r] = __builtin_fmaf(p, s, v[r]);
+        }
     }
 }
 
@@ -110,40 +145,34 @@ struct FwhtStages<VPL, LOGE, LOGSEG, LOGSEG> {
     static __device__ __forceinline__ void run(float (&)[VPL], int, int, int) {}
 };
 
-template <int LOGSEG, int IN, int OUT>
-__global__ void __launch_bounds__(LOGSEG >= 12 ? 512 : 1024)
-row_transform_kernel(RowArgs a, int segs, int rows_per_wg, float c_norm) {
+// Per-wave geometry shared by the phases of the kernel.
+struct RowCtx {
+    int lane, bperm_addr;
+    int64_t row, kbase;     // kbase: first element of this lane's chunk 0
+    bool row_ok;
+};
+
+// Load one segment into registers, rotate it, apply the fold vector; returns the local absmax (quantising kernels).
+// FAST: the row exists and the whole segment lies inside it, so nothing is bounds-checked.
+template <int LOGSEG, int IN, int OUT, bool FAST, int LB>
+__device__ __forceinline__ float row_phase1(const RowArgs& a, const RowCtx& x, float c_norm,
+                                            float (&v)[1 << (LOGSEG - 6)], float& sign_l, bool& fold_c) {
     constexpr int LOGE = (IN == IN_BF16) ? 3 : 2;
-    constexpr int EPL = 1 << LOGE;            // consecutive elements per lane per chunk
-    constexpr int VPL = 1 << (LOGSEG - 6);    // values per lane
-    constexpr int NCH = VPL / EPL;            // chunks per lane
-    constexpr int SEG = 1 << LOGSEG;
+    constexpr int EPL = 1 << LOGE;
+    constexpr int VPL = 1 << (LOGSEG - 6);
+    constexpr int NCH = VPL / EPL;
 
-    __shared__ float s_amax[16];
-
-    const int lane = threadIdx.x & 63;
-    const int wave = threadIdx.x >> 6;
-    const int seg = wave % segs;
-    const int row_local = wave / segs;
-    const int64_t row = (int64_t)blockIdx.x * rows_per_wg + row_local;
-    const bool row_ok = row < a.rows;
-    const int bperm_addr = (lane ^ 32) << 2;
-    const int64_t kbase = (int64_t)seg * SEG + (int64_t)lane * EPL;
-
-    float v[VPL];
-
-    // ------------------------------------------------------------------ load
     float pre = 1.0f;
     if constexpr (IN == IN_I32) {
-        if (row_ok && a.pre_scale) pre = a.pre_scale[row];
+        if (x.row_ok && a.pre_scale) pre = a.pre_scale[x.row];
     }
 #pragma unroll
     for (int c = 0; c < NCH; ++c) {
-        const int64_t k0 = kbase + (int64_t)c * 64 * EPL;
-        if (row_ok && k0 + EPL <= a.cols) {
+        const int64_t k0 = x.kbase + (int64_t)c * 64 * EPL;
+        if (FAST || (x.row_ok && k0 + EPL <= a.cols)) {
             if constexpr (IN == IN_BF16) {
                 const uint4 q = *reinterpret_cast<const uint4*>(
-                    reinterpret_cast<const uint16_t*>(a.in) + row * a.ld_in + k0);
+                    reinterpret_cast<const uint16_t*>(a.in) + x.row * a.ld_in + k0);
                 const uint32_t w[4] = {q.x, q.y, q.z, q.w};
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
@@ -152,11 +181,11 @@ row_transform_kernel(RowArgs a, int segs, int rows_per_wg, float c_norm) {
                 }
             } else if constexpr (IN == IN_F32) {
                 const float4 q = *reinterpret_cast<const float4*>(
-                    reinterpret_cast<const float*>(a.in) + row * a.ld_in + k0);
+                    reinterpret_cast<const float*>(a.in) + x.row * a.ld_in + k0);
                 v[c * EPL + 0] = q.x; v[c * EPL + 1] = q.y; v[c * EPL + 2] = q.z; v[c * EPL + 3] = q.w;
             } else {
                 const int4 q = *reinterpret_cast<const int4*>(
-                    reinterpret_cast<const int32_t*>(a.in) + row * a.ld_in + k0);
+                    reinterpret_cast<const int32_t*>(a.in) + x.row * a.ld_in + k0);
                 v[c * EPL + 0] = (float)q.x * pre; v[c * EPL + 1] = (float)q.y * pre;
                 v[c * EPL + 2] = (float)q.z * pre; v[c * EPL + 3] = (float)q.w * pre;
             }
@@ -164,13 +193,13 @@ row_transform_kernel(RowArgs a, int segs, int rows_per_wg, float c_norm) {
 #pragma unroll
             for (int e = 0; e < EPL; ++e) {
                 float t = 0.0f;
-                if (row_ok && k0 + e < a.cols) {
+                if (x.row_ok && k0 + e < a.cols) {
                     if constexpr (IN == IN_BF16) {
-                        t = __uint_as_float((uint32_t)(reinterpret_cast<const uint16_t*>(a.in)[row * a.ld_in + k0 + e]) << 16);
+                        t = __uint_as_float((uint32_t)(reinterpret_cast<const uint16_t*>(a.in)[x.row * a.ld_in + k0 + e]) << 16);
                     } else if constexpr (IN == IN_F32) {
-                        t = reinterpret_cast<const float*>(a.in)[row * a.ld_in + k0 + e];
+                        t = reinterpret_cast<const float*>(a.in)[x.row * a.ld_in + k0 + e];
                     } else {
-                        t = (float)reinterpret_cast<const int32_t*>(a.in)[row * a.ld_in + k0 + e] * pre;
+                        t = (float)reinterpret_cast<const int32_t*>(a.in)[x.row * a.ld_in + k0 + e] * pre;
                     }
                 }
                 v[c * EPL + e] = t;
@@ -178,25 +207,34 @@ row_transform_kernel(RowArgs a, int segs, int rows_per_wg, float c_norm) {
         }
     }
 
-    // ------------------------------------------------------------------ rotate
-    const int log_block = a.log_block;
+    // ---- rotate (LB >= 0: block size known at compile time, so the stage sequence is straight-line code)
+    const int log_block = LB >= 0 ? LB : a.log_block;
+    sign_l = 1.0f;       // pending per-lane sign of the register contents
+    fold_c = false;      // pending multiplication by c_norm
     if (log_block > 0) {
-        FwhtStages<VPL, LOGE, 0, LOGSEG>::run(v, log_block, lane, bperm_addr);
-        // lanes whose (lane & mask) has odd parity hold negated values; fold that into the normalisation
+        FwhtStages<VPL, LOGE, 0, LOGSEG>::run(v, log_block, x.lane, x.bperm_addr);
+        // lanes whose (lane & mask) has odd parity hold negated values
         int nlane_stages = log_block - LOGE;
         nlane_stages = nlane_stages < 0 ? 0 : (nlane_stages > 6 ? 6 : nlane_stages);
         const int mask = (1 << nlane_stages) - 1;
-        const float c_l = (__builtin_popcount(lane & mask) & 1) ? -c_norm : c_norm;
+        sign_l = (__builtin_popcount(x.lane & mask) & 1) ? -1.0f : 1.0f;
+        // 1/sqrt(d): one multiply per element, except that a power of two is folded into the quantiser scale
+        // (the same bits as long as nothing underflows, which the absmax test in the caller ensures).
+        fold_c = HALO_ROW_FOLD_C && OUT == OUT_Q8 && !a.fold && (log_block % 2 == 0);
+        if (!fold_c) {
+            const float c_l = sign_l * c_norm;
 #pragma unroll
-        for (int r = 0; r < VPL; ++r) v[r] *= c_l;
+            for (int r = 0; r < VPL; ++r) v[r] *= c_l;
+            sign_l = 1.0f;
+        }
     }
 
-    // ------------------------------------------------------------------ fold
+    // ---- fold
     if (a.fold) {
 #pragma unroll
         for (int c = 0; c < NCH; ++c) {
-            const int64_t k0 = kbase + (int64_t)c * 64 * EPL;
-            if (k0 + EPL <= a.cols) {
+            const int64_t k0 = x.kbase + (int64_t)c * 64 * EPL;
+            if (FAST || k0 + EPL <= a.cols) {
 #pragma unroll
                 for (int i = 0; i < EPL / 4; ++i) {
                     const float4 f = *reinterpret_cast<const float4*>(a.fold + k0 + 4 * i);
@@ -211,84 +249,85 @@ row_transform_kernel(RowArgs a, int segs, int rows_per_wg, float c_norm) {
         }
     }
 
-    // ------------------------------------------------------------------ store
+    float amax = 0.0f;
     if constexpr (OUT == OUT_Q8) {
-        float amax = 0.0f;
 #pragma unroll
-        for (int r = 0; r < VPL; ++r) amax = fmaxf(amax, fabsf(v[r]));
-        amax = wave_max(amax, bperm_addr);
-        if (segs > 1) {
-            if (lane == 0) s_amax[wave] = amax;
-            __syncthreads();
-            const int w0 = row_local * segs;
-            float t = s_amax[w0];
-            for (int i = 1; i < segs; ++i) t = fmaxf(t, s_amax[w0 + i]);
-            amax = t;
-        }
-        const bool nz = amax > 0.0f;
-        const float inv = nz ? 127.0f / amax : 0.0f;
-        if (row_ok && seg == 0 && lane == 0) a.out_scale[row] = nz ? amax / 127.0f : 1.0f;
-        int8_t* orow = reinterpret_cast<int8_t*>(a.out) + row * a.ld_out;
+        for (int r = 0; r < VPL; r += 2) amax = __builtin_fmaxf(amax, __builtin_fmaxf(fabsf(v[r]), fabsf(v[r + 1])));
+        amax = wave_max(amax, x.bperm_addr);
+    }
+    return amax;
+}
+
+// Quantise (inv_l = per-lane signed 127/absmax) or convert, and store the segment.
+template <int LOGSEG, int IN, int OUT, bool FAST>
+__device__ __forceinline__ void row_phase2(const RowArgs& a, const RowCtx& x, const float (&v)[1 << (LOGSEG - 6)],
+                                           float inv_l) {
+    constexpr int LOGE = (IN == IN_BF16) ? 3 : 2;
+    constexpr int EPL = 1 << LOGE;
+    constexpr int VPL = 1 << (LOGSEG - 6);
+    constexpr int NCH = VPL / EPL;
+    if constexpr (OUT == OUT_Q8) {
+        int8_t* orow = reinterpret_cast<int8_t*>(a.out) + x.row * a.ld_out;
 #pragma unroll
         for (int c = 0; c < NCH; ++c) {
-            const int64_t k0 = kbase + (int64_t)c * 64 * EPL;
+            const int64_t k0 = x.kbase + (int64_t)c * 64 * EPL;
             uint32_t packed[EPL / 4];
 #pragma unroll
             for (int i = 0; i < EPL / 4; ++i) {
                 uint32_t b[4];
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    const float t = v[c * EPL + 4 * i + e] * inv;
+                    const float t = v[c * EPL + 4 * i + e] * inv_l;
                     b[e] = __float_as_uint(t + kRoundMagic);
                 }
                 const uint32_t lo = __builtin_amdgcn_perm(b[1], b[0], 0x0c0c0400u);
                 const uint32_t hi = __builtin_amdgcn_perm(b[3], b[2], 0x0c0c0400u);
                 packed[i] = __builtin_amdgcn_perm(hi, lo, 0x05040100u);
             }
-            if (row_ok && k0 + EPL <= a.cols) {
+            if (FAST || (x.row_ok && k0 + EPL <= a.cols)) {
                 if constexpr (EPL == 8) {
                     *reinterpret_cast<uint2*>(orow + k0) = make_uint2(packed[0], packed[1]);
                 } else {
                     *reinterpret_cast<uint32_t*>(orow + k0) = packed[0];
                 }
-            } else if (row_ok) {
+            } else if (x.row_ok) {
 #pragma unroll
                 for (int e = 0; e < EPL; ++e)
                     if (k0 + e < a.cols) orow[k0 + e] = (int8_t)((packed[e / 4] >> (8 * (e & 3))) & 0xFF);
             }
         }
     } else if constexpr (OUT == OUT_BF16) {
-        uint16_t* orow = reinterpret_cast<uint16_t*>(a.out) + row * a.ld_out;
+        uint16_t* orow = reinterpret_cast<uint16_t*>(a.out) + x.row * a.ld_out;
 #pragma unroll
         for (int c = 0; c < NCH; ++c) {
-            const int64_t k0 = kbase + (int64_t)c * 64 * EPL;
+            const int64_t k0 = x.kbase + (int64_t)c * 64 * EPL;
             uint32_t packed[EPL / 2];
 #pragma unroll
             for (int i = 0; i < EPL / 2; ++i)
                 packed[i] = f32_to_bf16_rne(v[c * EPL + 2 * i]) | (f32_to_bf16_rne(v[c * EPL + 2 * i + 1]) << 16);
-            if (row_ok && k0 + EPL <= a.cols) {
+            if (FAST || (x.row_ok && k0 + EPL <= a.cols)) {
                 if constexpr (EPL == 8) {
                     *reinterpret_cast<uint4*>(orow + k0) = make_uint4(packed[0], packed[1], packed[2], packed[3]);
                 } else {
                     *reinterpret_cast<uint2*>(orow + k0) = make_uint2(packed[0], packed[1]);
                 }
-            } else if (row_ok) {
+            } else if (x.row_ok) {
 #pragma unroll
                 for (int e = 0; e < EPL; ++e)
                     if (k0 + e < a.cols) orow[k0 + e] = (uint16_t)(packed[e / 2] >> (16 * (e & 1)));
             }
         }
     } else {
-        float* orow = reinterpret_cast<float*>(a.out) + row * a.ld_out;
+        float* orow = reinterpret_cast<float*>(a.out) + x.row * a.ld_out;
 #pragma unroll
         for (int c = 0; c < NCH; ++c) {
-            const int64_t k0 = kbase + (int64_t)c * 64 * EPL;
-            if (row_ok && k0 + EPL <= a.cols) {
+            const int64_t k0 = x.kbase + (int64_t)c * 64 * EPL;
+            if (FAST || (x.row_ok && k0 + EPL <= a.cols)) {
 #pragma unroll
                 for (int i = 0; i < EPL / 4; ++i)
                     *reinterpret_cast<float4*>(orow + k0 + 4 * i) =
                         make_float4(v[c * EPL + 4 * i], v[c * EPL + 4 * i + 1], v[c * EPL + 4 * i + 2], v[c * EPL + 4 * i + 3]);
-            } else if (row_ok) {
+            } else if (x.row_ok) {
 #pragma unroll
                 for (int e = 0; e < EPL; ++e)
                     if (k0 + e < a.cols) orow[k0 + e] = v[c * EPL + e];
@@ -297,20 +336,83 @@ row_transform_kernel(RowArgs a, int segs, int rows_per_wg, float c_norm) {
     }
 }
 
+// LB: log2 of the Hadamard block when it is 0 (no rotation) or LOGSEG (block = segment); -1 = read it at run time.
+template <int LOGSEG, int IN, int OUT, int LB>
+__global__ void __launch_bounds__(LOGSEG >= 11 ? 512 : 1024)
+row_transform_kernel(RowArgs a, int segs, int rows_per_wg, float c_norm) {
+    constexpr int LOGE = (IN == IN_BF16) ? 3 : 2;
+    constexpr int EPL = 1 << LOGE;            // consecutive elements per lane per chunk
+    constexpr int VPL = 1 << (LOGSEG - 6);    // values per lane
+    constexpr int SEG = 1 << LOGSEG;
+
+    __shared__ float s_amax[16];
+
+    const int wave = threadIdx.x >> 6;
+    const int seg = wave % segs;
+    const int row_local = wave / segs;
+    RowCtx x;
+    x.lane = threadIdx.x & 63;
+    x.bperm_addr = (x.lane ^ 32) << 2;
+    x.row = (int64_t)blockIdx.x * rows_per_wg + row_local;
+    x.row_ok = x.row < a.rows;
+    x.kbase = (int64_t)seg * SEG + (int64_t)x.lane * EPL;
+    const bool fast = x.row_ok && ((int64_t)(seg + 1) * SEG <= a.cols);   // uniform over the wavefront
+
+    float v[VPL];
+    float sign_l;
+    bool fold_c;
+    float amax = fast ? row_phase1<LOGSEG, IN, OUT, true, LB>(a, x, c_norm, v, sign_l, fold_c)
+                      : row_phase1<LOGSEG, IN, OUT, false, LB>(a, x, c_norm, v, sign_l, fold_c);
+
+    float inv_l = 0.0f;
+    if constexpr (OUT == OUT_Q8) {
+        if (segs > 1) {
+            if (x.lane == 0) s_amax[wave] = amax;
+            __syncthreads();
+            const int w0 = row_local * segs;
+            float t = s_amax[w0];
+            for (int i = 1; i < segs; ++i) t = fmaxf(t, s_amax[w0 + i]);
+            amax = t;
+        }
+        float amax_t = amax;
+        if (fold_c) {
+            amax_t = amax * c_norm;                      // exact: c_norm is a power of two here
+            if (amax_t < 1e-30f && amax > 0.0f) {        // too close to underflow: take the plain path
+#pragma unroll
+                for (int r = 0; r < VPL; ++r) v[r] *= c_norm;
+                fold_c = false;
+            }
+        }
+        const bool nz = amax_t > 0.0f;
+        const float inv = nz ? 127.0f / amax_t : 0.0f;
+        inv_l = (fold_c ? inv * c_norm : inv) * sign_l;
+        if (x.row_ok && seg == 0 && x.lane == 0) a.out_scale[x.row] = nz ? amax_t / 127.0f : 1.0f;
+    }
+    if (fast) row_phase2<LOGSEG, IN, OUT, true>(a, x, v, inv_l);
+    else row_phase2<LOGSEG, IN, OUT, false>(a, x, v, inv_l);
+}
+
 template <int LOGSEG, int IN, int OUT>
 hipError_t launch_one(const RowArgs& a, int segs, hipStream_t s) {
     const int rows_per_wg = segs >= 4 ? 1 : 4 / segs;
     const int threads = 64 * segs * rows_per_wg;
     const int64_t blocks = (a.rows + rows_per_wg - 1) / rows_per_wg;
     const float c_norm = a.log_block > 0 ? (float)(1.0 / sqrt((double)(int64_t(1) << a.log_block))) : 1.0f;
-    hipLaunchKernelGGL((row_transform_kernel<LOGSEG, IN, OUT>), dim3((unsigned)blocks), dim3(threads), 0, s,
-                       a, segs, rows_per_wg, c_norm);
+    if (a.log_block == 0)
+        hipLaunchKernelGGL((row_transform_kernel<LOGSEG, IN, OUT, 0>), dim3((unsigned)blocks), dim3(threads), 0, s,
+                           a, segs, rows_per_wg, c_norm);
+    else if (a.log_block == LOGSEG)
+        hipLaunchKernelGGL((row_transform_kernel<LOGSEG, IN, OUT, LOGSEG>), dim3((unsigned)blocks), dim3(threads), 0, s,
+                           a, segs, rows_per_wg, c_norm);
+    else
+        hipLaunchKernelGGL((row_transform_kernel<LOGSEG, IN, OUT, -1>), dim3((unsigned)blocks), dim3(threads), 0, s,
+                           a, segs, rows_per_wg, c_norm);
     return hipGetLastError();
 }
 
 template <int IN, int OUT>
 hipError_t launch_by_seg(const RowArgs& a, hipStream_t s) {
-    // Segment = max(Hadamard block, 512), grown until the row fits the workgroup (16 waves, 8 at 4096).
+    // Segment = max(Hadamard block, 512), grown until the row fits the workgroup (16 waves, 8 from 2048 up).
     int logseg = a.log_block < 9 ? 9 : a.log_block;
     if (a.log_block == 0) {
         // no rotation: any segmentation is valid; 1024-element segments keep register use low
@@ -319,7 +421,7 @@ hipError_t launch_by_seg(const RowArgs& a, hipStream_t s) {
     for (;; ++logseg) {
         if (logseg > 12) return hipErrorInvalidValue;
         const int64_t segs = (a.cols + (int64_t(1) << logseg) - 1) >> logseg;
-        if (segs <= (logseg == 12 ? 8 : 16)) break;
+        if (segs <= (logseg >= 11 ? 8 : 16)) break;
     }
     const int segs = (int)((a.cols + (int64_t(1) << logseg) - 1) >> logseg);
     switch (logseg) {
