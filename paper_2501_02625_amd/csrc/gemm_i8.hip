@@ -58,7 +58,9 @@ struct GemmCfg {
     static constexpr int A_BYTES = BM * BK;
     static constexpr int B_BYTES = TRANSB ? BN * BK : (BK / 4) * LDB_NN * 4;
     static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
-    static constexpr int LDS_BYTES = NS * STAGE_BYTES;
+    static constexpr int EPI_PITCH = WN + 8;                     // dwords per row of the epilogue staging region
+    static constexpr int EPI_BYTES = WAVES_M * WAVES_N * 32 * EPI_PITCH * 4;
+    static constexpr int LDS_BYTES = NS * STAGE_BYTES > EPI_BYTES ? NS * STAGE_BYTES : EPI_BYTES;
     static constexpr int SLOTS_A = BM * CH / NT;
     static constexpr int SLOTS_B = BN * CH / NT;                 // transB
     static constexpr int BLKS_B = (BK / 4) * (BN / 4) / NT;      // !transB
@@ -172,35 +174,77 @@ __device__ __forceinline__ void mma_stage(const unsigned char* sa, const unsigne
     }
 }
 
+// Epilogue.  The accumulator layout (a lane owns one column of a 32x32 tile) would give 2- or 4-byte stores
+// scattered over 32 rows, so each wavefront first drops a 32-row slab of its sub-tile into a private LDS region
+// (one dword per element, row pitch WN+8 dwords: conflict-free writes) and reads it back four consecutive
+// columns per lane, which turns the global stores into 16-byte (int32/fp32) or 8-byte (bf16) pieces of fully
+// covered rows.  Only the owning wavefront touches its region, so no barrier is needed after the first one.
 template <class Cfg>
-__device__ __forceinline__ void epilogue(const GemmArgs& a, int64_t m0, int64_t n0, int wave_m, int wave_n, int lrow,
-                                         int half, const v16i (&acc)[Cfg::TM][Cfg::TN]) {
-    const bool scaled = a.C != nullptr;
+__device__ __forceinline__ void epilogue(const GemmArgs& a, int64_t m0, int64_t n0, int wave, int wave_m, int wave_n,
+                                         int lane, const v16i (&acc)[Cfg::TM][Cfg::TN], unsigned char* smem) {
+    constexpr int WN = Cfg::WN, PITCH = Cfg::EPI_PITCH;
+    constexpr int LPR = WN / 4;            // lanes per row when reading back
+    constexpr int RPP = 64 / LPR;          // rows per read-back pass
+    const int lrow = lane & 31, half = lane >> 5;
+    uint32_t* region = reinterpret_cast<uint32_t*>(smem) + wave * 32 * PITCH;
+    __syncthreads();                       // every wavefront is done with the operand stages
+
+    const int cc = (lane % LPR) * 4;
+    const int64_t col = n0 + wave_n * WN + cc;
+    const bool col_any = col < a.N, col_all = col + 4 <= a.N;
+    float cs[4] = {1.0f, 1.0f, 1.0f, 1.0f};
+    if (a.C && a.col_scale) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            if (col + e < a.N) cs[e] = a.col_scale[col + e];
+    }
 #pragma unroll
     for (int i = 0; i < Cfg::TM; ++i) {
-        float rs[16];
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int64_t row = m0 + wave_m * Cfg::WM + i * 32 + 8 * (r / 4) + 4 * half + (r % 4);
-            rs[r] = (scaled && a.row_scale && row < a.M) ? a.row_scale[row] : 1.0f;
-        }
+        for (int j = 0; j < Cfg::TN; ++j)
 #pragma unroll
-        for (int j = 0; j < Cfg::TN; ++j) {
-            const int64_t col = n0 + wave_n * Cfg::WN + j * 32 + lrow;
-            if (col >= a.N) continue;
-            const float cs = (scaled && a.col_scale) ? a.col_scale[col] : 1.0f;
+            for (int r = 0; r < 16; ++r)
+                region[(8 * (r / 4) + 4 * half + (r % 4)) * PITCH + j * 32 + lrow] = (uint32_t)acc[i][j][r];
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int64_t row = m0 + wave_m * Cfg::WM + i * 32 + 8 * (r / 4) + 4 * half + (r % 4);
-                if (row >= a.M) continue;
-                const int v = acc[i][j][r];
-                if (a.acc_out) a.acc_out[row * a.ld_acc + col] = v;
-                if (scaled) {
-                    const float f = ((float)v * rs[r]) * cs;
-                    if (a.c_is_f32) {
-                        reinterpret_cast<float*>(a.C)[row * a.ldc + col] = f;
+        for (int p = 0; p < 32 / RPP; ++p) {
+            const int rr = p * RPP + lane / LPR;
+            const int4 v = *reinterpret_cast<const int4*>(region + rr * PITCH + cc);
+            const int64_t row = m0 + wave_m * Cfg::WM + i * 32 + rr;
+            if (row >= a.M || !col_any) continue;
+            const int vv[4] = {v.x, v.y, v.z, v.w};
+            if (a.acc_out) {
+                int32_t* dst = a.acc_out + row * a.ld_acc + col;
+                if (col_all) {
+                    *reinterpret_cast<int4*>(dst) = v;
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (col + e < a.N) dst[e] = vv[e];
+                }
+            }
+            if (a.C) {
+                const float rs = a.row_scale ? a.row_scale[row] : 1.0f;
+                float f[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) f[e] = ((float)vv[e] * rs) * cs[e];
+                if (a.c_is_f32) {
+                    float* dst = reinterpret_cast<float*>(a.C) + row * a.ldc + col;
+                    if (col_all) {
+                        *reinterpret_cast<float4*>(dst) = make_float4(f[0], f[1], f[2], f[3]);
                     } else {
-                        reinterpret_cast<uint16_t*>(a.C)[row * a.ldc + col] = (uint16_t)f32_to_bf16_rne(f);
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (col + e < a.N) dst[e] = f[e];
+                    }
+                } else {
+                    uint16_t* dst = reinterpret_cast<uint16_t*>(a.C) + row * a.ldc + col;
+                    if (col_all) {
+                        *reinterpret_cast<uint2*>(dst) = make_uint2(f32_to_bf16_rne(f[0]) | (f32_to_bf16_rne(f[1]) << 16),
+                                                                     f32_to_bf16_rne(f[2]) | (f32_to_bf16_rne(f[3]) << 16));
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (col + e < a.N) dst[e] = (uint16_t)f32_to_bf16_rne(f[e]);
                     }
                 }
             }
@@ -387,7 +431,7 @@ gemm_i8_dma_kernel(GemmArgs a, int tiles_m, int tiles_n) {
         }
         asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
     }
-    epilogue<Cfg>(a, m0, n0, wave_m, wave_n, lrow, half, acc);
+    epilogue<Cfg>(a, m0, n0, wave, wave_m, wave_n, lane, acc, smem);
 }
 
 // ------------------------------------------------------------------------------------------------ staged main loop
@@ -520,7 +564,7 @@ gemm_i8_staged_kernel(GemmArgs a, int tiles_m, int tiles_n) {
             __syncthreads();
         }
     }
-    epilogue<Cfg>(a, m0, n0, wave_m, wave_n, lrow, half, acc);
+    epilogue<Cfg>(a, m0, n0, wave, wave_m, wave_n, lane, acc, smem);
 }
 
 // ------------------------------------------------------------------------------------------------ launch
@@ -558,7 +602,8 @@ hipError_t launch_staged(const GemmArgs& a, hipStream_t s) {
 
 // Configurations (macro tile M x N x K-step bytes, wavefronts, ring depth):
 //   0: 256x256x64  8w NS4     1: 256x128x64 8w NS4     2: 128x128x64 4w NS4     3: 128x256x64 8w NS4
-//   4: 256x256x128 8w NS2     5: 256x128x128 8w NS3
+//   4: 256x256x128 8w NS2     5: 256x128x128 8w(2x4) NS3   6: 256x128x128 4w(2x2) NS3
+//   7: 128x256x128 8w(2x4) NS3   8: 256x128x128 8w(4x2) NS3
 //   20..22: staged loops of 256x256x64 8w / 256x128x64 4w / 128x128x64 4w
 template <bool TRANSB>
 hipError_t launch_by_shape(const GemmArgs& a, hipStream_t s) {
@@ -588,6 +633,9 @@ hipError_t launch_by_shape(const GemmArgs& a, hipStream_t s) {
         case 3: return launch_dma<128, 256, 64, 2, 4, TRANSB, 4>(a, s);
         case 4: return launch_dma<256, 256, 128, 2, 4, TRANSB, 2>(a, s);
         case 5: return launch_dma<256, 128, 128, 2, 4, TRANSB, 3>(a, s);
+        case 6: return launch_dma<256, 128, 128, 2, 2, TRANSB, 3>(a, s);
+        case 7: return launch_dma<128, 256, 128, 2, 4, TRANSB, 3>(a, s);
+        case 8: return launch_dma<256, 128, 128, 4, 2, TRANSB, 3>(a, s);
         default: return hipErrorInvalidValue;
     }
 }
