@@ -37,6 +37,7 @@ namespace {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
+typedef int v2i __attribute__((ext_vector_type(2)));
 
 #define HALO_GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void*)(p))
 #define HALO_LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
@@ -46,8 +47,12 @@ __device__ __forceinline__ uint32_t f32_to_bf16_rne(float f) {
     return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
 }
 
-template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, bool TRANSB, int NS>
+// TR: the K-strided B operand goes to LDS untransposed (K-major rows of BN bytes, by DMA like A) and is transposed
+// by the LDS read itself (ds_read_b64_tr_b8).
+template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, bool TRANSB, int NS, bool TR = false>
 struct GemmCfg {
+    static constexpr bool IS_TR = TR;
+    static constexpr int BN_ = BN;
     static constexpr int NT = 64 * WAVES_M * WAVES_N;
     static constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
     static constexpr int TM = WM / 32, TN = WN / 32;
@@ -56,15 +61,18 @@ struct GemmCfg {
     static constexpr int KSTEPS = BK / 32;
     static constexpr int LDB_NN = BN + 8;     // dword pitch of the K-strided layout
     static constexpr int A_BYTES = BM * BK;
-    static constexpr int B_BYTES = TRANSB ? BN * BK : (BK / 4) * LDB_NN * 4;
+    static constexpr int CHB = BN / 16;       // 16-byte chunks per K-major row of B (TR)
+    static constexpr int RPSB = 256 / BN;     // K-major rows per 256-byte sweep of the LDS banks (TR)
+    static constexpr int B_BYTES = (TRANSB || TR) ? BN * BK : (BK / 4) * LDB_NN * 4;
     static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
     static constexpr int EPI_PITCH = WN + 8;                     // dwords per row of the epilogue staging region
     static constexpr int EPI_BYTES = WAVES_M * WAVES_N * 32 * EPI_PITCH * 4;
     static constexpr int LDS_BYTES = NS * STAGE_BYTES > EPI_BYTES ? NS * STAGE_BYTES : EPI_BYTES;
     static constexpr int SLOTS_A = BM * CH / NT;
-    static constexpr int SLOTS_B = BN * CH / NT;                 // transB
+    static constexpr int SLOTS_B = BN * CH / NT;                 // transB, and TR (BK rows of BN/16 chunks)
     static constexpr int BLKS_B = (BK / 4) * (BN / 4) / NT;      // !transB
-    static constexpr int NB = TRANSB ? SLOTS_B : BLKS_B;
+    static constexpr int NB = (TRANSB || TR) ? SLOTS_B : BLKS_B;
+    static_assert(!TR || (!TRANSB && (BN == 128 || BN == 256)), "TR is for the K-strided B operand");
     static_assert(BM * CH % NT == 0 && BN * CH % NT == 0, "tile/threads mismatch");
     static_assert(((BK / 4) * (BN / 4)) % NT == 0, "tile/threads mismatch");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
@@ -121,6 +129,22 @@ __device__ __forceinline__ void load_frags(const unsigned char* sa, const unsign
         if constexpr (TRANSB) {
             const int pc = g ^ ((col / RPS) % CH);
             bf[j] = *reinterpret_cast<const v4i*>(sb + col * BK + 16 * pc);
+        } else if constexpr (Cfg::IS_TR) {
+            // A group of 16 lanes reads an 8(k) x 16(n) byte block: lane i supplies the address of 8 bytes of
+            // K-major row k0 + i/2 at column offset 8*(i%2) and receives the 8 k-values of column i of the block.
+            // Rows are XOR-swizzled by 2*((row / RPSB) % (CHB/2)) chunks, which keeps the two lane groups of one
+            // read on even and odd chunks respectively (no bank conflicts) and is undone by the DMA addresses.
+            const int lane16 = (lrow & 15), gsel = lrow >> 4;
+            const int chunk = (wave_n * Cfg::WN + j * 32) / 16 + gsel;
+#pragma unroll
+            for (int q = 0; q < 2; ++q) {
+                const int krow = 32 * kk + 16 * half + 8 * q + (lane16 >> 1);
+                const int pc = chunk ^ (2 * ((krow / Cfg::RPSB) % (Cfg::CHB / 2)));
+                const v2i r = __builtin_amdgcn_ds_read_tr8_b64_v2i32(
+                    (__attribute__((address_space(3))) v2i*)(sb + krow * Cfg::BN_ + 16 * pc + 8 * (lane16 & 1)));
+                bf[j][2 * q] = r[0];
+                bf[j][2 * q + 1] = r[1];
+            }
         } else {
             const uint32_t* sbw = reinterpret_cast<const uint32_t*>(sb);
 #pragma unroll
@@ -152,7 +176,7 @@ template <class Cfg, bool TRANSB, int BK>
 __device__ __forceinline__ void mma_stage(const unsigned char* sa, const unsigned char* sb, int wave_m, int wave_n,
                                           int lrow, int half, v16i (&acc)[Cfg::TM][Cfg::TN]) {
     constexpr int TM = Cfg::TM, TN = Cfg::TN;
-    constexpr int READS = TM + (TRANSB ? TN : 4 * TN);     // LDS read instructions per sub-step
+    constexpr int READS = TM + (TRANSB ? TN : (Cfg::IS_TR ? 2 * TN : 4 * TN));     // LDS read instructions per sub-step
     constexpr int MFMAS = TM * TN;
     v4i af[2][TM], bf[2][TN];
     load_frags<Cfg, TRANSB, BK>(sa, sb, 0, wave_m, wave_n, lrow, half, af[0], bf[0]);
@@ -267,10 +291,11 @@ __device__ __forceinline__ void wait_vmcnt_lgkm0(int n) {
 }
 
 // ------------------------------------------------------------------------------------------------ dma main loop
-template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, bool TRANSB, int NS>
+template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, bool TRANSB, int NS, bool TR = false>
 __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N)
 gemm_i8_dma_kernel(GemmArgs a, int tiles_m, int tiles_n) {
-    using Cfg = GemmCfg<BM, BN, BK, WAVES_M, WAVES_N, TRANSB, NS>;
+    using Cfg = GemmCfg<BM, BN, BK, WAVES_M, WAVES_N, TRANSB, NS, TR>;
+    constexpr bool BOTH_DMA = TRANSB || TR;   // both operands go through the DMA ring
     constexpr int NT = Cfg::NT, CH = Cfg::CH, RPS = Cfg::RPS, TM = Cfg::TM, TN = Cfg::TN;
     constexpr int D = NS - 1;                                     // K steps in flight
     constexpr int LOADS = Cfg::SLOTS_A + Cfg::SLOTS_B;      // DMA loads per K step when both operands use the ring
@@ -318,6 +343,20 @@ gemm_i8_dma_kernel(GemmArgs a, int tiles_m, int tiles_n) {
             b_koff[i] = 16 * g;
             b_ok[i] = true;
         }
+    } else if constexpr (TR) {
+        // K-major rows of BN bytes; LDS slot (row, pc) holds chunk pc ^ swizzle(row) of that row.  A chunk whose
+        // columns start beyond the row pitch is replaced by chunk 0 (those columns are never stored).
+#pragma unroll
+        for (int i = 0; i < Cfg::SLOTS_B; ++i) {
+            const int p = tid + i * NT;
+            const int row = p / Cfg::CHB, pc = p % Cfg::CHB;
+            const int c = pc ^ (2 * ((row / Cfg::RPSB) % (Cfg::CHB / 2)));
+            int64_t colb = n0 + 16 * c;
+            if (colb >= a.ldb) colb = 0;
+            b_src[i] = a.B + (int64_t)row * a.ldb + colb;
+            b_koff[i] = row;
+            b_ok[i] = true;
+        }
     } else {
 #pragma unroll
         for (int i = 0; i < Cfg::BLKS_B; ++i) {
@@ -348,14 +387,21 @@ gemm_i8_dma_kernel(GemmArgs a, int tiles_m, int tiles_n) {
                 __builtin_amdgcn_global_load_lds(HALO_GLOBAL_PTR(b_src[i] + k0 + b_koff[i]),
                                                  HALO_LDS_PTR(sb + (wave * 64 + i * NT) * 16), 16, 0, 0);
             }
+        } else if constexpr (TR) {
+            unsigned char* sb = sa + Cfg::A_BYTES;
+#pragma unroll
+            for (int i = 0; i < Cfg::SLOTS_B; ++i) {
+                __builtin_amdgcn_global_load_lds(HALO_GLOBAL_PTR(b_src[i] + k0 * a.ldb),
+                                                 HALO_LDS_PTR(sb + (wave * 64 + i * NT) * 16), 16, 0, 0);
+            }
         }
     };
 
     // K-strided B: unconditional (address-clamped) dword loads so that the number of loads per K step is fixed;
     // rows beyond K and columns beyond N are zeroed after the load.
-    uint32_t b_raw[TRANSB ? 1 : Cfg::BLKS_B][4];
+    uint32_t b_raw[BOTH_DMA ? 1 : Cfg::BLKS_B][4];
     auto load_b_regs = [&](int t) {
-        if constexpr (!TRANSB) {
+        if constexpr (!BOTH_DMA) {
             const int64_t k0 = (int64_t)t * BK;
 #pragma unroll
             for (int i = 0; i < Cfg::BLKS_B; ++i) {
@@ -371,7 +417,7 @@ gemm_i8_dma_kernel(GemmArgs a, int tiles_m, int tiles_n) {
         }
     };
     auto store_b_lds = [&](int t) {
-        if constexpr (!TRANSB) {
+        if constexpr (!BOTH_DMA) {
             unsigned char* sb = smem + (t % NS) * Cfg::STAGE_BYTES + Cfg::A_BYTES;
 #pragma unroll
             for (int i = 0; i < Cfg::BLKS_B; ++i) {
@@ -391,7 +437,7 @@ gemm_i8_dma_kernel(GemmArgs a, int tiles_m, int tiles_n) {
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
 
     if (nk > 0) {
-        if constexpr (TRANSB) {
+        if constexpr (BOTH_DMA) {
             // prologue: K steps 0 .. D-1 in flight
             for (int t = 0; t < D && t < nk; ++t) issue_dma(t);
             for (int kt = 0; kt < nk; ++kt) {
@@ -569,6 +615,7 @@ gemm_i8_staged_kernel(GemmArgs a, int tiles_m, int tiles_n) {
 
 // ------------------------------------------------------------------------------------------------ launch
 int g_forced_config = -1;
+int g_nn_transpose_in_lds = 1;   // 0: transpose the K-strided operand in registers instead (measurement aid)
 
 template <class Kern>
 hipError_t launch_kernel(Kern kern, int lds_bytes, int threads, int bm, int bn, const GemmArgs& a, hipStream_t s,
@@ -586,6 +633,15 @@ hipError_t launch_kernel(Kern kern, int lds_bytes, int threads, int bm, int bn, 
 
 template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, bool TRANSB, int NS>
 hipError_t launch_dma(const GemmArgs& a, hipStream_t s) {
+    if constexpr (!TRANSB) {
+        // K-strided B: the LDS-transposing path needs whole K steps (it cannot zero-fill a K tail)
+        if (a.K % BK == 0 && g_nn_transpose_in_lds) {
+            using Cfg = GemmCfg<BM, BN, BK, WAVES_M, WAVES_N, false, NS, true>;
+            static bool attr_set_tr = false;
+            return launch_kernel(gemm_i8_dma_kernel<BM, BN, BK, WAVES_M, WAVES_N, false, NS, true>, Cfg::LDS_BYTES, Cfg::NT,
+                                 BM, BN, a, s, &attr_set_tr);
+        }
+    }
     using Cfg = GemmCfg<BM, BN, BK, WAVES_M, WAVES_N, TRANSB, NS>;
     static bool attr_set = false;
     return launch_kernel(gemm_i8_dma_kernel<BM, BN, BK, WAVES_M, WAVES_N, TRANSB, NS>, Cfg::LDS_BYTES, Cfg::NT, BM, BN,
@@ -642,7 +698,11 @@ hipError_t launch_by_shape(const GemmArgs& a, hipStream_t s) {
 
 }  // namespace
 
-void set_gemm_config(int cfg) { g_forced_config = cfg; }
+void set_gemm_config(int cfg) {
+    // bit 8 of a non-negative value selects the register-transposing variant of the K-strided path
+    g_nn_transpose_in_lds = !(cfg >= 0 && (cfg & 0x100));
+    g_forced_config = cfg >= 0 ? (cfg & 0xFF) : cfg;
+}
 
 hipError_t launch_gemm_i8(const GemmArgs& a, hipStream_t s) {
     if (a.M == 0 || a.N == 0) return hipSuccess;
