@@ -168,6 +168,11 @@ def main():
     add_hbm("hadamard_quant_cols_t(E,fold=s_x)", lambda i: (lambda: binding.halo_hadamard_quant(
         srcs[i], axis=binding.HALO_QUANT_COLS_T, fold=state.s_x, out_q=qts[i], out_scale=sts[i], workspace=wsc)),
         b * n * 3 + n * 4, k)
+    if level <= 1:
+        wsd = torch.empty((binding.load_library().halo_quant_dual_workspace_bytes(b, n),), dtype=torch.uint8, device=dev)
+        add_hbm("quant_dual(E,fold=s_w|s_x)", lambda i: (lambda: binding.halo_quant_dual(
+            srcs[i], fold_cols=state.s_w, fold_rows=state.s_x, out_q=qs[i], row_scale=ss[i], out_qt=qts[i],
+            col_scale=sts[i], workspace=wsd)), b * n * 4 + (b + n) * 4, k)
     del srcs, qs, ss, qts, sts
     if level >= 1:
         for nm, rows, acc, sc, out in (("dequant_unrotate(acc->EX)", b, acc_bm, None, EX), ("dequant_unrotate(acc->G)", n, acc_nm, None, G)):

@@ -92,6 +92,24 @@ halo_status halo_hadamard_quant(const void* in, halo_dtype in_dt, int64_t rows, 
                                 size_t workspace_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * halo_quant_dual: both quantisations of the output gradient E that levels 0 and 1 need, from one tiling of E.
+ * (Table "HALO levels": (E_Y)_Q for the E product and (E_Y^T)_Q for the G product.)
+ *
+ *   out_q  [rows x cols] = codes of  Q_row( in[r,k] * fold_cols[k] ),  row_scale[rows]
+ *   out_qT [cols x rows] = codes of  Q_row( (in[r,k] * fold_rows[r])^T ),  col_scale[cols]
+ * i.e. exactly what halo_hadamard_quant(HALO_QUANT_ROWS, fold = fold_cols) and
+ * halo_hadamard_quant(HALO_QUANT_COLS_T, fold = fold_rows) produce, bit for bit, with E read twice instead of
+ * three times and three kernels instead of five.  in is bf16; fold vectors are fp32 and may be NULL.
+ * workspace: halo_quant_dual_workspace_bytes(rows, cols) = 4*(rows+cols) bytes, rounded up.
+ */
+size_t halo_quant_dual_workspace_bytes(int64_t rows, int64_t cols);
+
+halo_status halo_quant_dual(const void* in, int64_t rows, int64_t cols, int64_t ld_in, const float* fold_cols,
+                            const float* fold_rows, int8_t* out_q, int64_t ld_q, float* row_scale,
+                            int8_t* out_qT, int64_t ld_qT, float* col_scale, void* workspace,
+                            size_t workspace_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
  * halo_gemm_i8: INT8 GEMM with int32 accumulation and a scaling epilogue.   (Section 2, Eqs. 1a-1c on
  * quantised operands; Table "HALO levels".)
  *

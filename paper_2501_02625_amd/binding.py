@@ -23,6 +23,7 @@ HALO_QUANT_ROWS, HALO_QUANT_COLS_T = 0, 1
 EXPORTED_SYMBOLS = (
     "halo_status_string", "halo_version",
     "halo_hadamard_quant_workspace_bytes", "halo_hadamard_quant",
+    "halo_quant_dual_workspace_bytes", "halo_quant_dual",
     "halo_gemm_i8", "halo_gemm_i8_set_config",
     "halo_dequant_unrotate_workspace_bytes", "halo_dequant_unrotate",
     "halo_linear_workspace_bytes", "halo_linear_fwd", "halo_linear_bwd",
@@ -65,6 +66,10 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.halo_hadamard_quant_workspace_bytes.argtypes = [i64, i64, c.c_int, i32]
     lib.halo_hadamard_quant.restype = c.c_int
     lib.halo_hadamard_quant.argtypes = [vp, c.c_int, i64, i64, i64, c.c_int, i32, i32, vp, vp, i64, vp, vp, sz, vp]
+    lib.halo_quant_dual_workspace_bytes.restype = sz
+    lib.halo_quant_dual_workspace_bytes.argtypes = [i64, i64]
+    lib.halo_quant_dual.restype = c.c_int
+    lib.halo_quant_dual.argtypes = [vp, i64, i64, i64, vp, vp, vp, i64, vp, vp, i64, vp, vp, sz, vp]
     lib.halo_gemm_i8.restype = c.c_int
     lib.halo_gemm_i8.argtypes = [vp, i64, vp, i64, c.c_int, i64, i64, i64, vp, vp, vp, c.c_int, i64, vp, i64, vp]
     lib.halo_gemm_i8_set_config.restype = None
@@ -149,6 +154,35 @@ def halo_hadamard_quant(x: torch.Tensor, *, axis: int = HALO_QUANT_ROWS, had_blo
                                  workspace.numel() if workspace is not None else 0, _stream())
     _check(st, "halo_hadamard_quant")
     return out_q, out_scale
+
+
+def halo_quant_dual(x: torch.Tensor, *, fold_cols: Optional[torch.Tensor] = None,
+                    fold_rows: Optional[torch.Tensor] = None, out_q: Optional[torch.Tensor] = None,
+                    row_scale: Optional[torch.Tensor] = None, out_qt: Optional[torch.Tensor] = None,
+                    col_scale: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None):
+    """Row-wise codes of x*fold_cols and transposed column-wise codes of x*fold_rows in one go.
+    Returns (codes [rows,cols], row_scale, codesT [cols,rows], col_scale)."""
+    lib = load_library()
+    _need_cuda(x, fold_cols, fold_rows, out_q, row_scale, out_qt, col_scale, workspace)
+    assert x.dim() == 2 and x.stride(1) == 1 and x.dtype == torch.bfloat16
+    rows, cols = x.shape
+    if out_q is None:
+        out_q = _empty_padded(rows, cols, torch.int8, x.device)
+    if out_qt is None:
+        out_qt = _empty_padded(cols, rows, torch.int8, x.device)
+    if row_scale is None:
+        row_scale = torch.empty((rows,), dtype=torch.float32, device=x.device)
+    if col_scale is None:
+        col_scale = torch.empty((cols,), dtype=torch.float32, device=x.device)
+    need = lib.halo_quant_dual_workspace_bytes(rows, cols)
+    if workspace is None:
+        workspace = torch.empty((max(need, 16),), dtype=torch.uint8, device=x.device)
+    st = lib.halo_quant_dual(_ptr(x), rows, cols, x.stride(0) if rows else cols, _ptr(fold_cols), _ptr(fold_rows),
+                             _ptr(out_q), out_q.stride(0) if out_q.numel() else max(cols, 16), _ptr(row_scale),
+                             _ptr(out_qt), out_qt.stride(0) if out_qt.numel() else max(rows, 16), _ptr(col_scale),
+                             _ptr(workspace), workspace.numel(), _stream())
+    _check(st, "halo_quant_dual")
+    return out_q, row_scale, out_qt, col_scale
 
 
 def halo_gemm_i8(a: torch.Tensor, b: torch.Tensor, *, trans_b: bool, row_scale: Optional[torch.Tensor] = None,

@@ -277,6 +277,174 @@ col_quant_t_kernel(const uint16_t* in, int64_t ld_in, int64_t rows, int64_t cols
     }
 }
 
+
+// ------------------------------------------------------------------------------------------------
+// Both quantisations of E that the backward pass needs, from one tiling of E:
+//   rows:  Eq [b x n]  = Q_row( E[i,j] * fold_c[j] )   (the saved weight scales folded in; feeds E_X = E W)
+//   cols:  EqT [n x b] = Q_row( (E[i,j] * fold_r[i])^T ) (the saved activation scales folded in; feeds G = E^T X)
+// Pass 1 accumulates both absmax vectors with integer atomic max on the bit patterns (exact, order-free); pass 2
+// re-reads E (cache-hot), emits the row-wise codes directly and the column-wise codes through an LDS transpose.
+constexpr int kAR = 32, kAC = 256;                               // absmax pass: tile rows, tile columns
+constexpr int kDR = 128, kDC = 128, kDPitch = kDR / 4 + 1;     // quantising pass: tile rows, columns, LDS dwords per column
+
+__device__ __forceinline__ float max_across_32(float x) {
+    // max over the 32 lanes that share (lane >> 5)
+    x = fmaxf(x, __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(x), 0xB1, 0xF, 0xF, true)));
+    x = fmaxf(x, __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(x), 0x4E, 0xF, 0xF, true)));
+    x = fmaxf(x, __int_as_float(__builtin_amdgcn_ds_swizzle(__float_as_int(x), 0x101F)));
+    x = fmaxf(x, __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(x), 0x128, 0xF, 0xF, true)));
+    x = fmaxf(x, __int_as_float(__builtin_amdgcn_ds_swizzle(__float_as_int(x), 0x401F)));
+    return x;
+}
+
+// Loads the 4 x 8 block (row quad iq, 8 columns from col) of E as fp32; out-of-range elements are zero.
+__device__ __forceinline__ void load_block(const uint16_t* in, int64_t ld_in, int64_t rows, int64_t cols, int64_t row0,
+                                           int64_t col, float (&x)[4][8]) {
+    const bool full = col + 8 <= cols;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int64_t row = row0 + r;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) x[r][e] = 0.0f;
+        if (row < rows && col < cols) {
+            const uint16_t* src = in + row * ld_in + col;
+            if (full) {
+                const uint4 w = *reinterpret_cast<const uint4*>(src);
+                const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    x[r][2 * i] = __uint_as_float(ww[i] << 16);
+                    x[r][2 * i + 1] = __uint_as_float(ww[i] & 0xFFFF0000u);
+                }
+            } else {
+                for (int e = 0; e < 8; ++e)
+                    if (col + e < cols) x[r][e] = __uint_as_float((uint32_t)src[e] << 16);
+            }
+        }
+    }
+}
+
+__global__ void __launch_bounds__(256)
+dual_amax_kernel(const uint16_t* in, int64_t ld_in, int64_t rows, int64_t cols, const float* fold_c, const float* fold_r,
+                 uint32_t* row_amax_bits, uint32_t* col_amax_bits) {
+    __shared__ float s_col[8][kAC];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int jl = tid & 31, rq = tid >> 5;             // 32 column groups of 8, 8 row quads
+    const int64_t col = (int64_t)blockIdx.x * kAC + 8 * jl;
+    const int64_t row0 = (int64_t)blockIdx.y * kAR + 4 * rq;
+    float fc[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) fc[e] = (fold_c && col + e < cols) ? fold_c[col + e] : 1.0f;
+    float cmax[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    float x[4][8];
+    load_block(in, ld_in, rows, cols, row0, col, x);
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const float fr = (fold_r && row0 + r < rows) ? fold_r[row0 + r] : 1.0f;
+        float rmax = 0.0f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            rmax = fmaxf(rmax, fabsf(x[r][e] * fc[e]));
+            cmax[e] = fmaxf(cmax[e], fabsf(x[r][e] * fr));
+        }
+        rmax = max_across_32(rmax);
+        if ((lane & 31) == 0 && row0 + r < rows && rmax > 0.0f) atomicMax(row_amax_bits + row0 + r, __float_as_uint(rmax));
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) s_col[rq][8 * jl + e] = cmax[e];
+    __syncthreads();
+    {
+        float t = s_col[0][tid];
+#pragma unroll
+        for (int q = 1; q < 8; ++q) t = fmaxf(t, s_col[q][tid]);
+        const int64_t c = (int64_t)blockIdx.x * kAC + tid;
+        if (c < cols && t > 0.0f) atomicMax(col_amax_bits + c, __float_as_uint(t));
+    }
+}
+
+__global__ void __launch_bounds__(256)
+dual_quant_kernel(const uint16_t* in, int64_t ld_in, int64_t rows, int64_t cols, const float* fold_c, const float* fold_r,
+                  const uint32_t* row_amax_bits, const uint32_t* col_amax_bits, int8_t* out_q, int64_t ld_q,
+                  float* row_scale, int8_t* out_qt, int64_t ld_qt, float* col_scale) {
+    __shared__ uint32_t s_tile[kDC * kDPitch];
+    const int tid = threadIdx.x;
+    const int jl = tid & 15, rq = tid >> 4;             // 16 column groups of 8, 16 row quads (two rounds)
+    const int64_t j0 = (int64_t)blockIdx.x * kDC, i0 = (int64_t)blockIdx.y * kDR;
+    const int64_t col = j0 + 8 * jl;
+    float fc[8], inv_c[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const bool ok = col + e < cols;
+        fc[e] = (fold_c && ok) ? fold_c[col + e] : 1.0f;
+        const float am = ok ? __uint_as_float(col_amax_bits[col + e]) : 0.0f;
+        inv_c[e] = am > 0.0f ? 127.0f / am : 0.0f;
+        if (blockIdx.y == 0 && rq == 0 && ok) col_scale[col + e] = am > 0.0f ? am / 127.0f : 1.0f;
+    }
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+        const int iq = rq + 16 * s;
+        const int64_t row0 = i0 + 4 * iq;
+        float x[4][8];
+        load_block(in, ld_in, rows, cols, row0, col, x);
+        uint32_t bc[4][8];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int64_t row = row0 + r;
+            const bool rok = row < rows;
+            const float fr = (fold_r && rok) ? fold_r[row] : 1.0f;
+            const float am = rok ? __uint_as_float(row_amax_bits[row]) : 0.0f;
+            const float inv_r = am > 0.0f ? 127.0f / am : 0.0f;
+            if (blockIdx.x == 0 && jl == 0 && rok) row_scale[row] = am > 0.0f ? am / 127.0f : 1.0f;
+            uint32_t br[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                br[e] = __float_as_uint((x[r][e] * fc[e]) * inv_r + 12582912.0f);
+                bc[r][e] = __float_as_uint((x[r][e] * fr) * inv_c[e] + 12582912.0f);
+            }
+            if (rok && col < cols) {
+                const uint32_t p0 = __builtin_amdgcn_perm(__builtin_amdgcn_perm(br[3], br[2], 0x0c0c0400u),
+                                                          __builtin_amdgcn_perm(br[1], br[0], 0x0c0c0400u), 0x05040100u);
+                const uint32_t p1 = __builtin_amdgcn_perm(__builtin_amdgcn_perm(br[7], br[6], 0x0c0c0400u),
+                                                          __builtin_amdgcn_perm(br[5], br[4], 0x0c0c0400u), 0x05040100u);
+                int8_t* dst = out_q + row * ld_q + col;
+                if (col + 8 <= cols) {
+                    *reinterpret_cast<uint2*>(dst) = make_uint2(p0, p1);
+                } else {
+                    for (int e = 0; e < 8; ++e)
+                        if (col + e < cols) dst[e] = (int8_t)(((e < 4 ? p0 : p1) >> (8 * (e & 3))) & 0xFF);
+                }
+            }
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const uint32_t lo = __builtin_amdgcn_perm(bc[1][e], bc[0][e], 0x0c0c0400u);
+            const uint32_t hi = __builtin_amdgcn_perm(bc[3][e], bc[2][e], 0x0c0c0400u);
+            s_tile[(8 * jl + e) * kDPitch + iq] = __builtin_amdgcn_perm(hi, lo, 0x05040100u);
+        }
+    }
+    __syncthreads();
+    {
+        const int seg = tid & 7;
+#pragma unroll
+        for (int s = 0; s < kDC / 32; ++s) {
+            const int jj = (tid >> 3) + 32 * s;
+            const int64_t c = j0 + jj;
+            if (c >= cols) continue;
+            uint32_t w[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) w[q] = s_tile[jj * kDPitch + 4 * seg + q];
+            const int64_t i = i0 + 16 * seg;
+            int8_t* dst = out_qt + c * ld_qt + i;
+            if (i + 16 <= rows) {
+                *reinterpret_cast<uint4*>(dst) = make_uint4(w[0], w[1], w[2], w[3]);
+            } else {
+                for (int e = 0; e < 16; ++e)
+                    if (i + e < rows) dst[e] = (int8_t)((w[e >> 2] >> (8 * (e & 3))) & 0xFF);
+            }
+        }
+    }
+}
+
 }  // namespace
 
 hipError_t launch_col_fwht(const ColFwhtArgs& a, hipStream_t s) {
@@ -313,6 +481,26 @@ hipError_t launch_col_fwht(const ColFwhtArgs& a, hipStream_t s) {
         p += sizes[i];
     }
     return hipSuccess;
+}
+
+hipError_t launch_dual_quant(const DualQuantArgs& a, hipStream_t s) {
+    if (a.rows == 0 || a.cols == 0) return hipSuccess;
+    uint32_t* row_bits = reinterpret_cast<uint32_t*>(a.amax_ws);          // [rows]
+    uint32_t* col_bits = row_bits + a.rows;                                // [cols]
+    const int64_t nfill = a.rows + a.cols;
+    hipLaunchKernelGGL(fill_u32_kernel, dim3((unsigned)((nfill + 255) / 256)), dim3(256), 0, s, row_bits, nfill, 0u);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const dim3 grid_a((unsigned)((a.cols + kAC - 1) / kAC), (unsigned)((a.rows + kAR - 1) / kAR));
+    const dim3 grid((unsigned)((a.cols + kDC - 1) / kDC), (unsigned)((a.rows + kDR - 1) / kDR));
+    const uint16_t* in = reinterpret_cast<const uint16_t*>(a.in);
+    hipLaunchKernelGGL(dual_amax_kernel, grid_a, dim3(256), 0, s, in, a.ld_in, a.rows, a.cols, a.fold_c, a.fold_r, row_bits,
+                       col_bits);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(dual_quant_kernel, grid, dim3(256), 0, s, in, a.ld_in, a.rows, a.cols, a.fold_c, a.fold_r, row_bits,
+                       col_bits, a.out_q, a.ld_q, a.row_scale, a.out_qt, a.ld_qt, a.col_scale);
+    return hipGetLastError();
 }
 
 hipError_t launch_col_quant_t(const ColQuantArgs& a, hipStream_t s) {

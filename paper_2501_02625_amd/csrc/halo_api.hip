@@ -67,7 +67,7 @@ BwdWorkspace bwd_layout(const halo_linear_desc* d) {
     w.s_e = off;  off += round256(b * 4);
     w.eqt = off;  off += round256(n * b);
     w.s_g = off;  off += round256(n * 4);
-    w.amax = off; off += round256(n * 4);
+    w.amax = off; off += round256((b + n) * 4);
     w.acc = off;  off += round256((b > n ? b : n) * m * 4);
     w.f32 = off;
     if (d->level >= 2) off += round256(b * (m > n ? m : n) * 4);
@@ -151,6 +151,30 @@ halo_status halo_hadamard_quant(const void* in, halo_dtype in_dt, int64_t rows, 
     if (e != hipSuccess) return HALO_EHIP;
     r.in = tmp; r.ld_in = cols;
     return from_hip(launch_row_transform(r, IN_F32, OUT_Q8, s));
+}
+
+// ------------------------------------------------------------------------------------------------
+size_t halo_quant_dual_workspace_bytes(int64_t rows, int64_t cols) {
+    if (rows <= 0 || cols <= 0) return 0;
+    return round256((size_t)(rows + cols) * 4);
+}
+
+halo_status halo_quant_dual(const void* in, int64_t rows, int64_t cols, int64_t ld_in, const float* fold_cols,
+                            const float* fold_rows, int8_t* out_q, int64_t ld_q, float* row_scale, int8_t* out_qT,
+                            int64_t ld_qT, float* col_scale, void* workspace, size_t workspace_bytes, void* stream) {
+    if (rows < 0 || cols < 0) return HALO_EINVAL;
+    if (rows == 0 || cols == 0) return HALO_OK;
+    if (!in || !out_q || !row_scale || !out_qT || !col_scale) return HALO_EINVAL;
+    if (rows > kMaxDim || cols > kMaxDim) return HALO_EUNSUPPORTED;
+    if (ld_in < cols || ld_q < cols || ld_qT < rows) return HALO_ESHAPE;
+    if (!aligned16(in) || !aligned16(out_q) || !aligned16(out_qT) || (ld_in * 2) % 16 || ld_q % 16 || ld_qT % 16)
+        return HALO_EALIGN;
+    const size_t need = halo_quant_dual_workspace_bytes(rows, cols);
+    if (!workspace || workspace_bytes < need) return HALO_EWORKSPACE;
+    if (!aligned16(workspace)) return HALO_EALIGN;
+    DualQuantArgs dq{in, ld_in, rows, cols, fold_cols, fold_rows, out_q, ld_q, row_scale, out_qT, ld_qT, col_scale,
+                     reinterpret_cast<float*>(workspace)};
+    return from_hip(launch_dual_quant(dq, reinterpret_cast<hipStream_t>(stream)));
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -281,11 +305,19 @@ halo_status halo_linear_bwd(const halo_linear_desc* desc, const void* E, const i
     int32_t* acc = reinterpret_cast<int32_t*>(ws + L.acc);
     float* f32 = reinterpret_cast<float*>(ws + L.f32);
 
+    // Levels 0 and 1 quantise the same E twice (per row for E_X, per column for G): one tiling of E does both.
+    const bool dual = EX && G && level <= 1;
+    if (dual) {
+        st = halo_quant_dual(E, b, n, n, s_w, s_x, Eq, n, s_e, EqT, b, s_g, amax, round256((size_t)(b + n) * 4), stream);
+        if (st != HALO_OK) return st;
+    }
     if (EX) {
         // (E_Y)_Q or (H E_Y)_Q with the saved weight scales folded in
-        st = halo_hadamard_quant(E, HALO_BF16, b, n, n, HALO_QUANT_ROWS, 0, level >= 2 ? hb : 0, s_w, Eq, n, s_e, f32,
-                                 level >= 2 ? round256((size_t)b * n * 4) : 0, stream);
-        if (st != HALO_OK) return st;
+        if (!dual) {
+            st = halo_hadamard_quant(E, HALO_BF16, b, n, n, HALO_QUANT_ROWS, 0, level >= 2 ? hb : 0, s_w, Eq, n, s_e, f32,
+                                     level >= 2 ? round256((size_t)b * n * 4) : 0, stream);
+            if (st != HALO_OK) return st;
+        }
         if (level == 0) {
             st = halo_gemm_i8(Eq, n, Wq, m, 0, b, m, n, s_e, nullptr, EX, odt, m, nullptr, 0, stream);
             if (st != HALO_OK) return st;
@@ -298,9 +330,11 @@ halo_status halo_linear_bwd(const halo_linear_desc* desc, const void* E, const i
         }
     }
     if (G) {
-        st = halo_hadamard_quant(E, HALO_BF16, b, n, n, HALO_QUANT_COLS_T, 0, 0, s_x, EqT, b, s_g, amax,
-                                 round256((size_t)n * 4), stream);
-        if (st != HALO_OK) return st;
+        if (!dual) {
+            st = halo_hadamard_quant(E, HALO_BF16, b, n, n, HALO_QUANT_COLS_T, 0, 0, s_x, EqT, b, s_g, amax,
+                                     round256((size_t)n * 4), stream);
+            if (st != HALO_OK) return st;
+        }
         if (level == 0) {
             st = halo_gemm_i8(EqT, b, Xq, m, 0, n, m, b, s_g, nullptr, G, odt, m, nullptr, 0, stream);
             if (st != HALO_OK) return st;

@@ -57,6 +57,23 @@ struct ColQuantArgs {
 };
 hipError_t launch_col_quant_t(const ColQuantArgs& a, hipStream_t s);
 
+// ---- both quantisations of E for the backward pass from one tiling (rows for E_X, transposed columns for G) ----
+struct DualQuantArgs {
+    const void* in;          // bf16 [rows x cols]
+    int64_t ld_in;
+    int64_t rows, cols;
+    const float* fold_c;     // per-column multiplier of the row-wise quantisation (saved weight scales), may be null
+    const float* fold_r;     // per-row multiplier of the column-wise quantisation (saved activation scales), may be null
+    int8_t* out_q;           // [rows x cols]
+    int64_t ld_q;
+    float* row_scale;        // [rows]
+    int8_t* out_qt;          // [cols x rows]
+    int64_t ld_qt;
+    float* col_scale;        // [cols]
+    float* amax_ws;          // [rows + cols] scratch
+};
+hipError_t launch_dual_quant(const DualQuantArgs& a, hipStream_t s);
+
 // ---- INT8 GEMM ----
 struct GemmArgs {
     const int8_t* A;

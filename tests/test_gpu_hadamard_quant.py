@@ -134,6 +134,32 @@ def test_col_quant_transposed_bit_exact(rows, cols):
     gu.assert_codes_equal(q, wq, "codes (no fold)"); gu.assert_f32_identical(s, ws, "scales (no fold)")
 
 
+@pytest.mark.parametrize("rows,cols", [(256, 512), (128, 256), (130, 200), (2048, 1024), (48, 4096), (1000, 24)])
+def test_quant_dual_matches_both_single_quantisers(rows, cols):
+    """One tiling of E gives (E_Y)_Q (weight scales folded per column) and (E_Y^T)_Q (activation scales per row)."""
+    e = inputs.make_errors(rows, cols, rows + 7 * cols)
+    fc = (np.abs(np.random.default_rng(3).standard_normal(cols)) * 1e-2 + 1e-4).astype(np.float32)
+    fr = (np.abs(np.random.default_rng(4).standard_normal(rows)) * 0.5 + 0.01).astype(np.float32)
+    e[:, 1] = 0                      # an all-zero column
+    if rows > 5:
+        e[5, :] = 0                  # and an all-zero row
+    ld = (cols + 7) // 8 * 8
+    x = torch.zeros((rows, ld), dtype=torch.bfloat16, device=gu.DEV)
+    x[:, :cols] = gu.bits_to_dev(e)
+    q, rs, qt, cs = binding.halo_quant_dual(x[:, :cols], fold_cols=gu.to_dev(fc), fold_rows=gu.to_dev(fr))
+    er = orc.bf16_bits_to_real(e)
+    wq, ws = orc.quantize_rows(er * fc[None, :])
+    wqt, wst = orc.quantize_rows(np.ascontiguousarray((er * fr[:, None]).T))
+    gu.assert_codes_equal(q, wq, "row codes"); gu.assert_f32_identical(rs, ws, "row scales")
+    gu.assert_codes_equal(qt, wqt, "column codes"); gu.assert_f32_identical(cs, wst, "column scales")
+    # no folds at all
+    q, rs, qt, cs = binding.halo_quant_dual(x[:, :cols])
+    wq, ws = orc.quantize_rows(er)
+    wqt, wst = orc.quantize_rows(np.ascontiguousarray(er.T))
+    gu.assert_codes_equal(q, wq, "row codes (no fold)"); gu.assert_f32_identical(rs, ws, "row scales (no fold)")
+    gu.assert_codes_equal(qt, wqt, "column codes (no fold)"); gu.assert_f32_identical(cs, wst, "column scales (no fold)")
+
+
 UNROT_CASES = [(64, 512, 512, 0), (33, 4096, 4096, 0), (8, 14336, 2048, 0), (256, 1024, 1024, 256),
                (4096, 256, 256, 4096), (50, 96, 0, 0), (2048, 512, 0, 2048)]
 
