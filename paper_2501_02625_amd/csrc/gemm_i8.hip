@@ -39,6 +39,10 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 typedef int v2i __attribute__((ext_vector_type(2)));
 
+#ifndef HALO_GEMM_SPREAD_DMA
+#define HALO_GEMM_SPREAD_DMA 1
+#endif
+
 #define HALO_GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void*)(p))
 #define HALO_LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
 
@@ -153,34 +157,46 @@ __device__ __forceinline__ void load_frags(const unsigned char* sa, const unsign
     }
 }
 
-// Scheduling recipe "one MFMA, then up to PER LDS reads", repeated: MFMAS matrix instructions, READS reads.
-template <int Q, int MFMAS, int READS>
-struct InterleaveSched {
+// Scheduling recipe for one LDS stage, written as sched_group_barrier groups in pipeline order:
+//   READS LDS reads (fragments of sub-step 0);
+//   for every sub-step but the last: MFMAS times { 1 MFMA, up to PER LDS reads (fragments of the next sub-step) },
+//                                    then the VM global->LDS DMA instructions the caller placed there;
+//   the MFMAs of the last sub-step.
+// Reads behind MFMAs keep the matrix pipe from draining while a wave waits for LDS; slicing the DMA instructions of
+// a K step over the sub-steps keeps the vector-memory queue from filling up in one burst.
+template <int IDX, int TOTAL, int MFMAS, int READS, int VM>
+struct StageSched {
     static __device__ __forceinline__ void run() {
+        constexpr int Q = IDX % MFMAS;                       // MFMA number inside its sub-step
         constexpr int PER = (READS + MFMAS - 1) / MFMAS;
         constexpr int LEFT = READS - Q * PER;
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
         if constexpr (LEFT > 0) __builtin_amdgcn_sched_group_barrier(0x100, LEFT < PER ? LEFT : PER, 0);
-        InterleaveSched<Q + 1, MFMAS, READS>::run();
+        if constexpr (VM > 0 && Q == MFMAS - 1) __builtin_amdgcn_sched_group_barrier(0x020, VM, 0);
+        StageSched<IDX + 1, TOTAL, MFMAS, READS, VM>::run();
     }
 };
-template <int MFMAS, int READS>
-struct InterleaveSched<MFMAS, MFMAS, READS> {
-    static __device__ __forceinline__ void run() {}
+template <int TOTAL, int MFMAS, int READS, int VM>
+struct StageSched<TOTAL, TOTAL, MFMAS, READS, VM> {
+    static __device__ __forceinline__ void run() { __builtin_amdgcn_sched_group_barrier(0x008, MFMAS, 0); }
+};
+
+struct NoBetween {
+    __device__ __forceinline__ void operator()(int) const {}
 };
 
 // All MFMAs of one LDS stage; the fragments of sub-step kk+1 are requested while the MFMAs of sub-step kk run.
-// The sched_group_barrier sequence pins that interleaving (LDS reads behind each MFMA) so that the matrix
-// pipe does not drain while a wave waits for LDS.
-template <class Cfg, bool TRANSB, int BK>
+// between(kk) is called after the MFMAs of sub-step kk (all but the last): the DMA kernels issue a slice of the
+// next K step's global->LDS loads there; VM = number of such instructions per call (for the scheduling recipe).
+template <class Cfg, bool TRANSB, int BK, int VM = 0, class Between = NoBetween>
 __device__ __forceinline__ void mma_stage(const unsigned char* sa, const unsigned char* sb, int wave_m, int wave_n,
-                                          int lrow, int half, v16i (&acc)[Cfg::TM][Cfg::TN]) {
+                                          int lrow, int half, v16i (&acc)[Cfg::TM][Cfg::TN],
+                                          const Between& between = Between()) {
     constexpr int TM = Cfg::TM, TN = Cfg::TN;
     constexpr int READS = TM + (TRANSB ? TN : (Cfg::IS_TR ? 2 * TN : 4 * TN));     // LDS read instructions per sub-step
     constexpr int MFMAS = TM * TN;
     v4i af[2][TM], bf[2][TN];
     load_frags<Cfg, TRANSB, BK>(sa, sb, 0, wave_m, wave_n, lrow, half, af[0], bf[0]);
-    __builtin_amdgcn_sched_group_barrier(0x100, READS, 0);
 #pragma unroll
     for (int kk = 0; kk < Cfg::KSTEPS; ++kk) {
         if (kk + 1 < Cfg::KSTEPS)
@@ -190,12 +206,10 @@ __device__ __forceinline__ void mma_stage(const unsigned char* sa, const unsigne
 #pragma unroll
             for (int j = 0; j < TN; ++j)
                 acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[kk & 1][i], bf[kk & 1][j], acc[i][j], 0, 0, 0);
-        if (kk + 1 < Cfg::KSTEPS) {
-            InterleaveSched<0, MFMAS, READS>::run();
-        } else {
-            __builtin_amdgcn_sched_group_barrier(0x008, MFMAS, 0);
-        }
+        if (kk + 1 < Cfg::KSTEPS) between(kk);
     }
+    __builtin_amdgcn_sched_group_barrier(0x100, READS, 0);
+    StageSched<0, (Cfg::KSTEPS - 1) * MFMAS, MFMAS, READS, VM>::run();
 }
 
 // Epilogue.  The accumulator layout (a lane owns one column of a 32x32 tile) would give 2- or 4-byte stores
@@ -370,11 +384,14 @@ gemm_i8_dma_kernel(GemmArgs a, int tiles_m, int tiles_n) {
 
     // DMA of the K-contiguous operand(s) of K step t into ring slot t % NS.  A chunk that lies beyond K (only
     // possible for A of the K-strided case, where the matching B rows are zero) is fetched from offset 0 instead.
-    auto issue_dma = [&](int t) {
+    // lo..hi select a sub-range of the step's DMA instructions (A slots first, then B slots), so that the caller
+    // can thread them between the MFMAs instead of issuing one burst.
+    auto issue_dma = [&](int t, int src_step = -1, int lo = 0, int hi = 1 << 20) {
         unsigned char* sa = smem + (t % NS) * Cfg::STAGE_BYTES;
-        const int64_t k0 = (int64_t)t * BK;
+        const int64_t k0 = (int64_t)(src_step < 0 ? t : src_step) * BK;
 #pragma unroll
         for (int i = 0; i < Cfg::SLOTS_A; ++i) {
+            if (i < lo || i >= hi) continue;
             int64_t k = k0 + a_koff[i];
             if (k >= a.K) k = 0;
             __builtin_amdgcn_global_load_lds(HALO_GLOBAL_PTR(a_src[i] + k),
@@ -384,6 +401,7 @@ gemm_i8_dma_kernel(GemmArgs a, int tiles_m, int tiles_n) {
             unsigned char* sb = sa + Cfg::A_BYTES;
 #pragma unroll
             for (int i = 0; i < Cfg::SLOTS_B; ++i) {
+                if (Cfg::SLOTS_A + i < lo || Cfg::SLOTS_A + i >= hi) continue;
                 __builtin_amdgcn_global_load_lds(HALO_GLOBAL_PTR(b_src[i] + k0 + b_koff[i]),
                                                  HALO_LDS_PTR(sb + (wave * 64 + i * NT) * 16), 16, 0, 0);
             }
@@ -391,6 +409,7 @@ gemm_i8_dma_kernel(GemmArgs a, int tiles_m, int tiles_n) {
             unsigned char* sb = sa + Cfg::A_BYTES;
 #pragma unroll
             for (int i = 0; i < Cfg::SLOTS_B; ++i) {
+                if (Cfg::SLOTS_A + i < lo || Cfg::SLOTS_A + i >= hi) continue;
                 __builtin_amdgcn_global_load_lds(HALO_GLOBAL_PTR(b_src[i] + k0 * a.ldb),
                                                  HALO_LDS_PTR(sb + (wave * 64 + i * NT) * 16), 16, 0, 0);
             }
@@ -438,18 +457,24 @@ gemm_i8_dma_kernel(GemmArgs a, int tiles_m, int tiles_n) {
 
     if (nk > 0) {
         if constexpr (BOTH_DMA) {
-            // prologue: K steps 0 .. D-1 in flight
-            for (int t = 0; t < D && t < nk; ++t) issue_dma(t);
+            // Every iteration issues exactly one K step (beyond the end: the last step again, into a ring slot
+            // nobody reads), so the loop body is one straight block with a constant wait count.
+            for (int t = 0; t < D; ++t) issue_dma(t, t < nk ? t : nk - 1);
             for (int kt = 0; kt < nk; ++kt) {
-                // K steps issued after kt and still allowed in flight: kt+1 .. min(kt+D-1, nk-1)
-                int later = nk - 1 - kt;
-                if (later > D - 1) later = D - 1;
-                wait_vmcnt_lgkm0(later * LOADS);
+                asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"((D - 1) * LOADS) : "memory");
                 __builtin_amdgcn_s_barrier();
                 asm volatile("" ::: "memory");
-                if (kt + D < nk) issue_dma(kt + D);        // ring slot (kt-1) % NS: everyone is past reading it
+                // ring slot (kt-1) % NS: everyone is past reading it
+                const int src = kt + D < nk ? kt + D : nk - 1;
                 const unsigned char* sa = smem + (kt % NS) * Cfg::STAGE_BYTES;
-                mma_stage<Cfg, TRANSB, BK>(sa, sa + Cfg::A_BYTES, wave_m, wave_n, lrow, half, acc);
+                if constexpr (HALO_GEMM_SPREAD_DMA && Cfg::KSTEPS > 1 && LOADS % (Cfg::KSTEPS - 1) == 0) {
+                    constexpr int PER = LOADS / (Cfg::KSTEPS - 1);
+                    auto between = [&](int kk) { issue_dma(kt + D, src, kk * PER, (kk + 1) * PER); };
+                    mma_stage<Cfg, TRANSB, BK, PER>(sa, sa + Cfg::A_BYTES, wave_m, wave_n, lrow, half, acc, between);
+                } else {
+                    issue_dma(kt + D, src);
+                    mma_stage<Cfg, TRANSB, BK>(sa, sa + Cfg::A_BYTES, wave_m, wave_n, lrow, half, acc);
+                }
             }
         } else {
             // A: DMA ring, D K steps in flight.  B: registers, loaded one K step ahead of the LDS write that
@@ -659,7 +684,8 @@ hipError_t launch_staged(const GemmArgs& a, hipStream_t s) {
 // Configurations (macro tile M x N x K-step bytes, wavefronts, ring depth):
 //   0: 256x256x64  8w NS4     1: 256x128x64 8w NS4     2: 128x128x64 4w NS4     3: 128x256x64 8w NS4
 //   4: 256x256x128 8w NS2     5: 256x128x128 8w(2x4) NS3   6: 256x128x128 4w(2x2) NS3
-//   7: 128x256x128 8w(2x4) NS3   8: 256x128x128 8w(4x2) NS3
+//   7: 128x256x128 8w(2x4) NS3   8: 256x128x128 8w(4x2) NS3   9: 128x128x64 4w NS3   10: 128x256x64 8w NS3
+//   11: 256x128x64 8w(4x2) NS3
 //   20..22: staged loops of 256x256x64 8w / 256x128x64 4w / 128x128x64 4w
 template <bool TRANSB>
 hipError_t launch_by_shape(const GemmArgs& a, hipStream_t s) {
@@ -668,9 +694,8 @@ hipError_t launch_by_shape(const GemmArgs& a, hipStream_t s) {
     if (cfg < 0) {
         // Enough 256x256 tiles to fill the 256 CUs: largest tile, 128-byte K steps.  Otherwise halve the tile
         // in N; small problems take 128x128 tiles.
-        if (tiles(256, 256) >= 200) cfg = 4;
-        else if (tiles(256, 128) >= 200) cfg = 5;
-        else cfg = 2;
+        if (TRANSB) cfg = tiles(256, 256) >= 200 ? 4 : (tiles(256, 128) >= 200 ? 8 : 2);
+        else cfg = tiles(256, 256) >= 200 ? 0 : 2;
     }
     // The DMA loop cannot zero-fill a K tail when both operands are K-contiguous.
     const bool dma_ok = !TRANSB || (a.K % 128 == 0);
@@ -692,6 +717,9 @@ hipError_t launch_by_shape(const GemmArgs& a, hipStream_t s) {
         case 6: return launch_dma<256, 128, 128, 2, 2, TRANSB, 3>(a, s);
         case 7: return launch_dma<128, 256, 128, 2, 4, TRANSB, 3>(a, s);
         case 8: return launch_dma<256, 128, 128, 4, 2, TRANSB, 3>(a, s);
+        case 9: return launch_dma<128, 128, 64, 2, 2, TRANSB, 3>(a, s);
+        case 10: return launch_dma<128, 256, 64, 2, 4, TRANSB, 3>(a, s);
+        case 11: return launch_dma<256, 128, 64, 4, 2, TRANSB, 3>(a, s);
         default: return hipErrorInvalidValue;
     }
 }
