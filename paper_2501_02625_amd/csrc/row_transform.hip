@@ -148,13 +148,15 @@ struct FwhtStages<VPL, LOGE, LOGSEG, LOGSEG> {
 // Per-wave geometry shared by the phases of the kernel.
 struct RowCtx {
     int lane, bperm_addr;
+    int wave, seg;          // wavefront in the workgroup; segment of the row it owns
+    float* xbuf;            // LDS exchange buffer [waves][values per lane][64] (only with cross-wave stages)
     int64_t row, kbase;     // kbase: first element of this lane's chunk 0
     bool row_ok;
 };
 
 // Load one segment into registers, rotate it, apply the fold vector; returns the local absmax (quantising kernels).
 // FAST: the row exists and the whole segment lies inside it, so nothing is bounds-checked.
-template <int LOGSEG, int IN, int OUT, bool FAST, int LB>
+template <int LOGSEG, int IN, int OUT, bool FAST, int LB, int XS>
 __device__ __forceinline__ float row_phase1(const RowArgs& a, const RowCtx& x, float c_norm,
                                             float (&v)[1 << (LOGSEG - 6)], float& sign_l, bool& fold_c) {
     constexpr int LOGE = (IN == IN_BF16) ? 3 : 2;
@@ -213,6 +215,25 @@ __device__ __forceinline__ float row_phase1(const RowArgs& a, const RowCtx& x, f
     fold_c = false;      // pending multiplication by c_norm
     if (log_block > 0) {
         FwhtStages<VPL, LOGE, 0, LOGSEG>::run(v, log_block, x.lane, x.bperm_addr);
+        if constexpr (XS > 0) {
+            // Strides 2^LOGSEG .. 2^(LOGSEG+XS-1) pair up whole segments, i.e. wavefronts of this workgroup: each
+            // wavefront publishes its registers in LDS and combines them with its partner's, the lower segment
+            // taking a+b and the upper one a-b (the lane signs carried so far are the same in both).
+#pragma unroll
+            for (int xs = 0; xs < XS; ++xs) {
+                if (xs > 0) __syncthreads();        // everyone has read the previous round
+#pragma unroll
+                for (int r = 0; r < VPL; ++r) x.xbuf[(x.wave * VPL + r) * 64 + x.lane] = v[r];
+                __syncthreads();
+                const bool upper = (x.seg >> xs) & 1;
+                const int pw = x.wave ^ (1 << xs);
+#pragma unroll
+                for (int r = 0; r < VPL; ++r) {
+                    const float p = x.xbuf[(pw * VPL + r) * 64 + x.lane];
+                    v[r] = upper ? p - v[r] : v[r] + p;
+                }
+            }
+        }
         // lanes whose (lane & mask) has odd parity hold negated values
         int nlane_stages = log_block - LOGE;
         nlane_stages = nlane_stages < 0 ? 0 : (nlane_stages > 6 ? 6 : nlane_stages);
@@ -337,7 +358,8 @@ __device__ __forceinline__ void row_phase2(const RowArgs& a, const RowCtx& x, co
 }
 
 // LB: log2 of the Hadamard block when it is 0 (no rotation) or LOGSEG (block = segment); -1 = read it at run time.
-template <int LOGSEG, int IN, int OUT, int LB>
+// XS: number of butterfly stages that span wavefronts (Hadamard block = 2^(LOGSEG+XS) elements = 2^XS segments).
+template <int LOGSEG, int IN, int OUT, int LB, int XS = 0>
 __global__ void __launch_bounds__(LOGSEG >= 11 ? 512 : 1024)
 row_transform_kernel(RowArgs a, int segs, int rows_per_wg, float c_norm) {
     constexpr int LOGE = (IN == IN_BF16) ? 3 : 2;
@@ -346,11 +368,15 @@ row_transform_kernel(RowArgs a, int segs, int rows_per_wg, float c_norm) {
     constexpr int SEG = 1 << LOGSEG;
 
     __shared__ float s_amax[16];
+    extern __shared__ float s_xbuf[];
 
     const int wave = threadIdx.x >> 6;
     const int seg = wave % segs;
     const int row_local = wave / segs;
     RowCtx x;
+    x.wave = wave;
+    x.seg = seg;
+    x.xbuf = s_xbuf;
     x.lane = threadIdx.x & 63;
     x.bperm_addr = (x.lane ^ 32) << 2;
     x.row = (int64_t)blockIdx.x * rows_per_wg + row_local;
@@ -361,8 +387,8 @@ row_transform_kernel(RowArgs a, int segs, int rows_per_wg, float c_norm) {
     float v[VPL];
     float sign_l;
     bool fold_c;
-    float amax = fast ? row_phase1<LOGSEG, IN, OUT, true, LB>(a, x, c_norm, v, sign_l, fold_c)
-                      : row_phase1<LOGSEG, IN, OUT, false, LB>(a, x, c_norm, v, sign_l, fold_c);
+    float amax = fast ? row_phase1<LOGSEG, IN, OUT, true, LB, XS>(a, x, c_norm, v, sign_l, fold_c)
+                      : row_phase1<LOGSEG, IN, OUT, false, LB, XS>(a, x, c_norm, v, sign_l, fold_c);
 
     float inv_l = 0.0f;
     if constexpr (OUT == OUT_Q8) {
@@ -392,6 +418,27 @@ row_transform_kernel(RowArgs a, int segs, int rows_per_wg, float c_norm) {
     else row_phase2<LOGSEG, IN, OUT, false>(a, x, v, inv_l);
 }
 
+#ifndef HALO_ROW_SPLIT
+#define HALO_ROW_SPLIT 2      // 0: never split a Hadamard block over wavefronts, 1: whenever possible, 2: by size
+#endif
+
+// Hadamard block of 2^(10+XS) elements handled by 2^XS wavefronts of 1024 elements each: four times the
+// wavefronts of the one-wavefront-per-block layout and a quarter of the registers, at the price of XS round trips
+// through LDS.  It pays when there are too few rows to fill the machine otherwise.
+template <int IN, int OUT, int XS>
+hipError_t launch_split(const RowArgs& a, hipStream_t s) {
+    constexpr int LOGSEG = 10;
+    const int segs = (int)(a.cols >> LOGSEG);
+    const int rows_per_wg = segs >= 4 ? 1 : 4 / segs;
+    const int threads = 64 * segs * rows_per_wg;
+    const int64_t blocks = (a.rows + rows_per_wg - 1) / rows_per_wg;
+    const float c_norm = (float)(1.0 / sqrt((double)(int64_t(1) << a.log_block)));
+    const size_t lds = (size_t)(threads / 64) * (1 << (LOGSEG - 6)) * 64 * sizeof(float);
+    hipLaunchKernelGGL((row_transform_kernel<LOGSEG, IN, OUT, LOGSEG + XS, XS>), dim3((unsigned)blocks), dim3(threads), lds,
+                       s, a, segs, rows_per_wg, c_norm);
+    return hipGetLastError();
+}
+
 template <int LOGSEG, int IN, int OUT>
 hipError_t launch_one(const RowArgs& a, int segs, hipStream_t s) {
     const int rows_per_wg = segs >= 4 ? 1 : 4 / segs;
@@ -412,6 +459,16 @@ hipError_t launch_one(const RowArgs& a, int segs, hipStream_t s) {
 
 template <int IN, int OUT>
 hipError_t launch_by_seg(const RowArgs& a, hipStream_t s) {
+    // Split blocks of 2048 / 4096 over 2 / 4 wavefronts (measured): the 32-bit-input un-rotation gains at every size
+    // for 4096-blocks (5.7 vs 5.2 TB/s at 32768 rows, 12.7 vs 16.0 us at 2048 rows); the quantiser only when whole
+    // rows would leave the 1024 SIMDs with fewer than four wavefronts each.
+    if (HALO_ROW_SPLIT && (a.log_block == 11 || a.log_block == 12) && a.cols % 1024 == 0 && a.cols <= 16384) {
+        const int64_t wavefronts_unsplit = a.rows * (a.cols >> a.log_block);
+        const bool want = IN == IN_I32 ? a.log_block == 12 : wavefronts_unsplit < 4096;
+        if (HALO_ROW_SPLIT == 1 || want) {
+            return a.log_block == 11 ? launch_split<IN, OUT, 1>(a, s) : launch_split<IN, OUT, 2>(a, s);
+        }
+    }
     // Segment = max(Hadamard block, 512), grown until the row fits the workgroup (16 waves, 8 from 2048 up).
     int logseg = a.log_block < 9 ? 9 : a.log_block;
     if (a.log_block == 0) {
