@@ -100,7 +100,7 @@ halo_status halo_hadamard_quant(const void* in, halo_dtype in_dt, int64_t rows, 
  * i.e. exactly what halo_hadamard_quant(HALO_QUANT_ROWS, fold = fold_cols) and
  * halo_hadamard_quant(HALO_QUANT_COLS_T, fold = fold_rows) produce, bit for bit, with E read twice instead of
  * three times and three kernels instead of five.  in is bf16; fold vectors are fp32 and may be NULL.
- * workspace: halo_quant_dual_workspace_bytes(rows, cols) = 4*(rows+cols) bytes, rounded up.
+ * workspace: halo_quant_dual_workspace_bytes(rows, cols) bytes (partial maxima per 32 x 256 tile).
  */
 size_t halo_quant_dual_workspace_bytes(int64_t rows, int64_t cols);
 

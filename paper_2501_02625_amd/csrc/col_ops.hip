@@ -324,9 +324,11 @@ __device__ __forceinline__ void load_block(const uint16_t* in, int64_t ld_in, in
     }
 }
 
+// Pass 1: every workgroup writes the partial maxima of its 32 x 256 tile (no atomics: device-scope atomics are
+// resolved beyond the per-XCD L2 and cost more than the whole pass): row_part[row][column tile], col_part[row tile][col].
 __global__ void __launch_bounds__(256)
 dual_amax_kernel(const uint16_t* in, int64_t ld_in, int64_t rows, int64_t cols, const float* fold_c, const float* fold_r,
-                 uint32_t* row_amax_bits, uint32_t* col_amax_bits) {
+                 float* row_part, float* col_part) {
     __shared__ float s_col[8][kAC];
     const int tid = threadIdx.x, lane = tid & 63;
     const int jl = tid & 31, rq = tid >> 5;             // 32 column groups of 8, 8 row quads
@@ -348,7 +350,7 @@ dual_amax_kernel(const uint16_t* in, int64_t ld_in, int64_t rows, int64_t cols, 
             cmax[e] = fmaxf(cmax[e], fabsf(x[r][e] * fr));
         }
         rmax = max_across_32(rmax);
-        if ((lane & 31) == 0 && row0 + r < rows && rmax > 0.0f) atomicMax(row_amax_bits + row0 + r, __float_as_uint(rmax));
+        if ((lane & 31) == 0 && row0 + r < rows) row_part[(row0 + r) * gridDim.x + blockIdx.x] = rmax;
     }
 #pragma unroll
     for (int e = 0; e < 8; ++e) s_col[rq][8 * jl + e] = cmax[e];
@@ -358,27 +360,56 @@ dual_amax_kernel(const uint16_t* in, int64_t ld_in, int64_t rows, int64_t cols, 
 #pragma unroll
         for (int q = 1; q < 8; ++q) t = fmaxf(t, s_col[q][tid]);
         const int64_t c = (int64_t)blockIdx.x * kAC + tid;
-        if (c < cols && t > 0.0f) atomicMax(col_amax_bits + c, __float_as_uint(t));
+        if (c < cols) col_part[(int64_t)blockIdx.y * cols + c] = t;
     }
 }
 
 __global__ void __launch_bounds__(256)
 dual_quant_kernel(const uint16_t* in, int64_t ld_in, int64_t rows, int64_t cols, const float* fold_c, const float* fold_r,
-                  const uint32_t* row_amax_bits, const uint32_t* col_amax_bits, int8_t* out_q, int64_t ld_q,
+                  const float* row_part, const float* col_part, int col_tiles, int row_tiles, int8_t* out_q, int64_t ld_q,
                   float* row_scale, int8_t* out_qt, int64_t ld_qt, float* col_scale) {
     __shared__ uint32_t s_tile[kDC * kDPitch];
+    __shared__ float s_red[2][2][128];     // [row/col][half][index]
+    __shared__ float s_amax_c[kDC], s_amax_r[kDR];
     const int tid = threadIdx.x;
     const int jl = tid & 15, rq = tid >> 4;             // 16 column groups of 8, 16 row quads (two rounds)
     const int64_t j0 = (int64_t)blockIdx.x * kDC, i0 = (int64_t)blockIdx.y * kDR;
     const int64_t col = j0 + 8 * jl;
+    // Absmax of this tile's 128 columns and 128 rows from the partial maxima of pass 1 (every workgroup redoes the
+    // reduction it needs: 40 KB of L2 hits instead of one more kernel between the passes).
+    {
+        const int o = tid & 127, h = tid >> 7;
+        float tc = 0.0f, tr = 0.0f;
+        if (j0 + o < cols) {
+#pragma unroll 16
+            for (int q = h; q < row_tiles; q += 2) tc = fmaxf(tc, col_part[(int64_t)q * cols + j0 + o]);
+        }
+        if (i0 + o < rows) {
+#pragma unroll 8
+            for (int q = h; q < col_tiles; q += 2) tr = fmaxf(tr, row_part[(i0 + o) * col_tiles + q]);
+        }
+        s_red[0][h][o] = tc;
+        s_red[1][h][o] = tr;
+        __syncthreads();
+        if (tid < 128) {
+            const float am = fmaxf(s_red[0][0][tid], s_red[0][1][tid]);
+            s_amax_c[tid] = am;
+            if (blockIdx.y == 0 && j0 + tid < cols) col_scale[j0 + tid] = am > 0.0f ? am / 127.0f : 1.0f;
+        } else {
+            const int r = tid - 128;
+            const float am = fmaxf(s_red[1][0][r], s_red[1][1][r]);
+            s_amax_r[r] = am;
+            if (blockIdx.x == 0 && i0 + r < rows) row_scale[i0 + r] = am > 0.0f ? am / 127.0f : 1.0f;
+        }
+        __syncthreads();
+    }
     float fc[8], inv_c[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
         const bool ok = col + e < cols;
         fc[e] = (fold_c && ok) ? fold_c[col + e] : 1.0f;
-        const float am = ok ? __uint_as_float(col_amax_bits[col + e]) : 0.0f;
+        const float am = s_amax_c[8 * jl + e];
         inv_c[e] = am > 0.0f ? 127.0f / am : 0.0f;
-        if (blockIdx.y == 0 && rq == 0 && ok) col_scale[col + e] = am > 0.0f ? am / 127.0f : 1.0f;
     }
 #pragma unroll
     for (int s = 0; s < 2; ++s) {
@@ -392,9 +423,8 @@ dual_quant_kernel(const uint16_t* in, int64_t ld_in, int64_t rows, int64_t cols,
             const int64_t row = row0 + r;
             const bool rok = row < rows;
             const float fr = (fold_r && rok) ? fold_r[row] : 1.0f;
-            const float am = rok ? __uint_as_float(row_amax_bits[row]) : 0.0f;
+            const float am = s_amax_r[4 * iq + r];
             const float inv_r = am > 0.0f ? 127.0f / am : 0.0f;
-            if (blockIdx.x == 0 && jl == 0 && rok) row_scale[row] = am > 0.0f ? am / 127.0f : 1.0f;
             uint32_t br[8];
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
@@ -483,23 +513,25 @@ hipError_t launch_col_fwht(const ColFwhtArgs& a, hipStream_t s) {
     return hipSuccess;
 }
 
+size_t dual_quant_workspace_floats(int64_t rows, int64_t cols) {
+    const int64_t col_tiles = (cols + kAC - 1) / kAC, row_tiles = (rows + kAR - 1) / kAR;
+    return (size_t)(rows * col_tiles + row_tiles * cols);
+}
+
 hipError_t launch_dual_quant(const DualQuantArgs& a, hipStream_t s) {
     if (a.rows == 0 || a.cols == 0) return hipSuccess;
-    uint32_t* row_bits = reinterpret_cast<uint32_t*>(a.amax_ws);          // [rows]
-    uint32_t* col_bits = row_bits + a.rows;                                // [cols]
-    const int64_t nfill = a.rows + a.cols;
-    hipLaunchKernelGGL(fill_u32_kernel, dim3((unsigned)((nfill + 255) / 256)), dim3(256), 0, s, row_bits, nfill, 0u);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    const dim3 grid_a((unsigned)((a.cols + kAC - 1) / kAC), (unsigned)((a.rows + kAR - 1) / kAR));
+    const int64_t col_tiles = (a.cols + kAC - 1) / kAC, row_tiles = (a.rows + kAR - 1) / kAR;
+    float* row_part = a.amax_ws;                                           // [rows][col_tiles]
+    float* col_part = row_part + a.rows * col_tiles;                       // [row_tiles][cols]
+    const dim3 grid_a((unsigned)col_tiles, (unsigned)row_tiles);
     const dim3 grid((unsigned)((a.cols + kDC - 1) / kDC), (unsigned)((a.rows + kDR - 1) / kDR));
     const uint16_t* in = reinterpret_cast<const uint16_t*>(a.in);
-    hipLaunchKernelGGL(dual_amax_kernel, grid_a, dim3(256), 0, s, in, a.ld_in, a.rows, a.cols, a.fold_c, a.fold_r, row_bits,
-                       col_bits);
-    e = hipGetLastError();
+    hipLaunchKernelGGL(dual_amax_kernel, grid_a, dim3(256), 0, s, in, a.ld_in, a.rows, a.cols, a.fold_c, a.fold_r, row_part,
+                       col_part);
+    hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(dual_quant_kernel, grid, dim3(256), 0, s, in, a.ld_in, a.rows, a.cols, a.fold_c, a.fold_r, row_bits,
-                       col_bits, a.out_q, a.ld_q, a.row_scale, a.out_qt, a.ld_qt, a.col_scale);
+    hipLaunchKernelGGL(dual_quant_kernel, grid, dim3(256), 0, s, in, a.ld_in, a.rows, a.cols, a.fold_c, a.fold_r, row_part,
+                       col_part, (int)col_tiles, (int)row_tiles, a.out_q, a.ld_q, a.row_scale, a.out_qt, a.ld_qt, a.col_scale);
     return hipGetLastError();
 }
 

@@ -67,7 +67,7 @@ BwdWorkspace bwd_layout(const halo_linear_desc* d) {
     w.s_e = off;  off += round256(b * 4);
     w.eqt = off;  off += round256(n * b);
     w.s_g = off;  off += round256(n * 4);
-    w.amax = off; off += round256((b + n) * 4);
+    w.amax = off; off += round256(dual_quant_workspace_floats(d->b, d->n) * 4);
     w.acc = off;  off += round256((b > n ? b : n) * m * 4);
     w.f32 = off;
     if (d->level >= 2) off += round256(b * (m > n ? m : n) * 4);
@@ -156,7 +156,7 @@ halo_status halo_hadamard_quant(const void* in, halo_dtype in_dt, int64_t rows, 
 // ------------------------------------------------------------------------------------------------
 size_t halo_quant_dual_workspace_bytes(int64_t rows, int64_t cols) {
     if (rows <= 0 || cols <= 0) return 0;
-    return round256((size_t)(rows + cols) * 4);
+    return round256(dual_quant_workspace_floats(rows, cols) * 4);
 }
 
 halo_status halo_quant_dual(const void* in, int64_t rows, int64_t cols, int64_t ld_in, const float* fold_cols,
@@ -308,7 +308,7 @@ halo_status halo_linear_bwd(const halo_linear_desc* desc, const void* E, const i
     // Levels 0 and 1 quantise the same E twice (per row for E_X, per column for G): one tiling of E does both.
     const bool dual = EX && G && level <= 1;
     if (dual) {
-        st = halo_quant_dual(E, b, n, n, s_w, s_x, Eq, n, s_e, EqT, b, s_g, amax, round256((size_t)(b + n) * 4), stream);
+        st = halo_quant_dual(E, b, n, n, s_w, s_x, Eq, n, s_e, EqT, b, s_g, amax, halo_quant_dual_workspace_bytes(b, n), stream);
         if (st != HALO_OK) return st;
     }
     if (EX) {

@@ -70,8 +70,9 @@ struct DualQuantArgs {
     int8_t* out_qt;          // [cols x rows]
     int64_t ld_qt;
     float* col_scale;        // [cols]
-    float* amax_ws;          // [rows + cols] scratch
+    float* amax_ws;          // dual_quant_workspace_floats(rows, cols) floats of scratch
 };
+size_t dual_quant_workspace_floats(int64_t rows, int64_t cols);
 hipError_t launch_dual_quant(const DualQuantArgs& a, hipStream_t s);
 
 // ---- INT8 GEMM ----

@@ -76,7 +76,7 @@ def test_quant_dual_argument_errors(lib):
     f = lib.halo_quant_dual
     A, Q, S, T, U, W = _p(0x1000), _p(0x2000), _p(0x3000), _p(0x4000), _p(0x5000), _p(0x6000)
     need = lib.halo_quant_dual_workspace_bytes(64, 512)
-    assert need >= 4 * (64 + 512)
+    assert need >= 4 * 64 * 2
     assert f(None, 64, 512, 512, None, None, Q, 512, S, T, 64, U, W, need, None) == binding.HALO_EINVAL
     assert f(A, 64, 512, 256, None, None, Q, 512, S, T, 64, U, W, need, None) == binding.HALO_ESHAPE
     assert f(A, 64, 512, 512, None, None, Q, 512, S, T, 48, U, W, need, None) == binding.HALO_ESHAPE
