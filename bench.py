@@ -33,6 +33,11 @@ def parse():
     p.add_argument("--config", default="c2", help="workload key from paper_2501_02625_amd.inputs.CONFIGS (single-linear ones)")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--kernel-iters", type=int, default=50, help="launches per kernel for the per-kernel timings")
+    p.add_argument("--pmc-target", default="",
+                   help="run ONE kernel family --steps times and exit (for rocprofv3 --pmc runs): gemm_fwd, gemm_ex, "
+                        "gemm_g, rowquant_x, rowquant_w, quant_dual, unrotate_ex, unrotate_g, copy")
+    p.add_argument("--step-only", action="store_true",
+                   help="time the step loop only (no per-kernel loops, no oracle): what a kernel-trace profile of the step needs")
     return p.parse_args()
 
 
@@ -93,6 +98,39 @@ def main():
         binding.halo_linear_fwd(desc, X, W, state=state, Y=Y)
         binding.halo_linear_bwd(desc, E, state, workspace=ws, EX=EX, G=G)
 
+    if args.pmc_target:
+        # One kernel family, a few launches, nothing else: the dispatches a counter run should see.
+        Eq_ = torch.randint(-127, 128, (b, n), dtype=torch.int8, device=dev)
+        EqT_ = torch.randint(-127, 128, (n, b), dtype=torch.int8, device=dev)
+        acc1 = torch.empty((b, m), dtype=torch.int32, device=dev)
+        acc2 = torch.empty((n, m), dtype=torch.int32, device=dev)
+        sc1 = torch.rand((b,), dtype=torch.float32, device=dev)
+        sc2 = torch.rand((n,), dtype=torch.float32, device=dev)
+        binding.halo_linear_fwd(desc, X, W, state=state, Y=Y)
+        src = torch.empty((64 << 20,), dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        wsd = torch.empty((binding.load_library().halo_quant_dual_workspace_bytes(b, n),), dtype=torch.uint8, device=dev)
+        qd = [torch.empty((b, n), dtype=torch.int8, device=dev), torch.empty((b,), dtype=torch.float32, device=dev),
+              torch.empty((n, b), dtype=torch.int8, device=dev), torch.empty((n,), dtype=torch.float32, device=dev)]
+        targets = {
+            "gemm_fwd": lambda: binding.halo_gemm_i8(state.Xq, state.Wq, trans_b=True, row_scale=state.s_x, col_scale=state.s_w, out=Y),
+            "gemm_ex": lambda: binding.halo_gemm_i8(Eq_, state.Wq, trans_b=False, out_dtype=None, acc_out=acc1),
+            "gemm_g": lambda: binding.halo_gemm_i8(EqT_, state.Xq, trans_b=False, out_dtype=None, acc_out=acc2),
+            "rowquant_x": lambda: binding.halo_hadamard_quant(X, had_block=hm, out_q=state.Xq, out_scale=state.s_x),
+            "rowquant_w": lambda: binding.halo_hadamard_quant(W, had_block=hm, out_q=state.Wq, out_scale=state.s_w),
+            "quant_dual": lambda: binding.halo_quant_dual(E, fold_cols=state.s_w, fold_rows=state.s_x, out_q=qd[0], row_scale=qd[1],
+                                                          out_qt=qd[2], col_scale=qd[3], workspace=wsd),
+            "unrotate_ex": lambda: binding.halo_dequant_unrotate(acc1, sc1, had_block=hm, out=EX),
+            "unrotate_g": lambda: binding.halo_dequant_unrotate(acc2, sc2, had_block=hm, out=G),
+            "copy": lambda: dst.copy_(src),      # plain device copy of 64 MiB: calibrates FETCH_SIZE / WRITE_SIZE
+        }
+        fn = targets[args.pmc_target]
+        for _ in range(args.steps):
+            fn()
+        torch.cuda.synchronize()
+        print(json.dumps({"pmc_target": args.pmc_target, "launches": args.steps}))
+        return
+
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -104,6 +142,12 @@ def main():
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     ops = 6.0 * b * n * m
     value = ops / (ms_per_step * 1e-3) / 1e12
+
+    if args.step_only:
+        print(json.dumps({"metric": "HALO linear fwd+bwd INT8 TOPS at Llama-3-8B shapes; Hadamard+quant GB/s",
+                          "value": value, "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+                          "ms_per_step": ms_per_step, "higher_is_better": True, "step_only": True}))
+        return
 
     # ---------------------------------------------------------------- per-kernel timings (HIP events)
     it = args.kernel_iters
@@ -188,8 +232,16 @@ def main():
             del accs, outs
 
     dominant = max(kernels, key=lambda k: k["ms"])
+    # HBM traffic of the dominant kernel from the committed rocprofv3 FETCH_SIZE / WRITE_SIZE summary (config c2 only)
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic_%s.json" % args.config)
+    if os.path.exists(tpath):
+        with open(tpath) as f:
+            tk = json.load(f)["kernels"].get(dominant["name"])
+        if tk:
+            traffic = tk["fetch_bytes"] + tk["write_bytes"]
     roofline = dict(kernel=dominant["name"], bound=dominant["bound"], achieved=dominant["achieved"], peak=dominant["peak"],
-                    unit=dominant["unit"], frac=dominant["frac"], traffic=None, avg_ms=dominant["ms"])
+                    unit=dominant["unit"], frac=dominant["frac"], traffic=traffic, avg_ms=dominant["ms"])
     hq = [k for k in kernels if k["name"].startswith("hadamard_quant_rows(X)")][0]
 
     # ---------------------------------------------------------------- oracle on the host cores
