@@ -219,16 +219,17 @@ def main():
             col_scale=sts[i], workspace=wsd)), b * n * 4 + (b + n) * 4, k)
     del srcs, qs, ss, qts, sts
     if level >= 1:
-        for nm, rows, acc, sc, out in (("dequant_unrotate(acc->EX)", b, acc_bm, None, EX), ("dequant_unrotate(acc->G)", n, acc_nm, None, G)):
+        for nm, rows, acc, left, out in (("dequant_unrotate(acc->EX%s)" % (",left" if hb else ""), b, acc_bm, hb, EX),
+                                         ("dequant_unrotate(acc->G)", n, acc_nm, 0, G)):
             nbytes = rows * m * (4 + 2)
             k = nrot(nbytes)
             accs = [acc] + [acc.clone() for _ in range(k - 1)]
             outs = [torch.empty((rows, m), dtype=torch.bfloat16, device=dev) for _ in range(k)]
             scale = torch.rand((rows,), dtype=torch.float32, device=dev)
-            wsu = torch.empty((max(1, binding.load_library().halo_dequant_unrotate_workspace_bytes(rows, m, hb if rows == b else 0)),),
+            wsu = torch.empty((max(1, binding.load_library().halo_dequant_unrotate_workspace_bytes(rows, m, left)),),
                               dtype=torch.uint8, device=dev)
-            add_hbm(nm, lambda i, accs=accs, outs=outs, scale=scale, wsu=wsu, rows=rows: (lambda: binding.halo_dequant_unrotate(
-                accs[i], scale, had_block=hm, had_block_left=(hb if rows == b else 0), out=outs[i], workspace=wsu)), nbytes, k)
+            add_hbm(nm, lambda i, accs=accs, outs=outs, scale=scale, wsu=wsu, left=left: (lambda: binding.halo_dequant_unrotate(
+                accs[i], scale, had_block=hm, had_block_left=left, out=outs[i], workspace=wsu)), nbytes, k)
             del accs, outs
 
     dominant = max(kernels, key=lambda k: k["ms"])
