@@ -6,6 +6,10 @@
 
 using namespace halo;
 
+#ifndef HALO_BATCH_ROWS
+#define HALO_BATCH_ROWS 1     // one row-kernel launch for X and W (forward) and for both accumulators (backward, level 1)
+#endif
+
 namespace {
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -27,7 +31,7 @@ constexpr int64_t kMaxLeftBlock = 65536;
 constexpr int64_t kMaxDim = int64_t(1) << 22;   // rows / columns of any matrix argument
 
 struct BwdWorkspace {
-    size_t eq, s_e, eqt, s_g, amax, acc, f32, total;
+    size_t eq, s_e, eqt, s_g, amax, acc, acc_g, f32, total;
 };
 
 inline int32_t default_block(int64_t len, int64_t cap) {
@@ -68,7 +72,8 @@ BwdWorkspace bwd_layout(const halo_linear_desc* d) {
     w.eqt = off;  off += round256(n * b);
     w.s_g = off;  off += round256(n * 4);
     w.amax = off; off += round256(dual_quant_workspace_floats(d->b, d->n) * 4);
-    w.acc = off;  off += round256((b > n ? b : n) * m * 4);
+    w.acc = off;  off += round256(b * m * 4);       // accumulators of the E product
+    w.acc_g = off; off += round256(n * m * 4);      // accumulators of the G product
     w.f32 = off;
     if (d->level >= 2) off += round256(b * (m > n ? m : n) * 4);
     w.total = off;
@@ -269,6 +274,15 @@ halo_status halo_linear_fwd(const halo_linear_desc* desc, const void* X, const v
     if ((X && !aligned16(X)) || (W && !aligned16(W)) || !aligned16(Y) || !aligned16(Xq) || !aligned16(Wq))
         return HALO_EALIGN;
     const halo_dtype odt = (halo_dtype)desc->out_dt;
+    if (HALO_BATCH_ROWS && X && W && m <= kMaxRowCols) {
+        // X and W get the same treatment: one launch rotates and quantises both
+        RowArgs r{};
+        r.in = X; r.ld_in = m; r.rows = b; r.cols = m; r.out = Xq; r.ld_out = m; r.out_scale = s_x;
+        r.log_block = hm ? ilog2_exact(hm) : 0;
+        r.rows2 = n; r.in2 = W; r.out2 = Wq; r.out_scale2 = s_w;
+        if (launch_row_transform(r, IN_BF16, OUT_Q8, reinterpret_cast<hipStream_t>(stream)) != hipSuccess) return HALO_EHIP;
+        return halo_gemm_i8(Xq, m, Wq, m, 1, b, n, m, s_x, s_w, Y, odt, n, nullptr, 0, stream);
+    }
     if (X) {
         st = halo_hadamard_quant(X, HALO_BF16, b, m, m, HALO_QUANT_ROWS, hm, 0, nullptr, Xq, m, s_x, nullptr, 0, stream);
         if (st != HALO_OK) return st;
@@ -303,6 +317,7 @@ halo_status halo_linear_bwd(const halo_linear_desc* desc, const void* E, const i
     float* s_g = reinterpret_cast<float*>(ws + L.s_g);
     float* amax = reinterpret_cast<float*>(ws + L.amax);
     int32_t* acc = reinterpret_cast<int32_t*>(ws + L.acc);
+    int32_t* acc_g = reinterpret_cast<int32_t*>(ws + L.acc_g);
     float* f32 = reinterpret_cast<float*>(ws + L.f32);
 
     // Levels 0 and 1 quantise the same E twice (per row for E_X, per column for G): one tiling of E does both.
@@ -324,9 +339,11 @@ halo_status halo_linear_bwd(const halo_linear_desc* desc, const void* E, const i
         } else {
             st = halo_gemm_i8(Eq, n, Wq, m, 0, b, m, n, nullptr, nullptr, nullptr, odt, 0, acc, m, stream);
             if (st != HALO_OK) return st;
-            st = halo_dequant_unrotate(acc, m, b, m, s_e, hm, level >= 2 ? hb : 0, EX, odt, m, f32,
-                                       level >= 2 ? round256((size_t)b * m * 4) : 0, stream);
-            if (st != HALO_OK) return st;
+            if (!(HALO_BATCH_ROWS && level == 1 && G)) {      // at level 1 with both products, one launch un-rotates both accumulators below
+                st = halo_dequant_unrotate(acc, m, b, m, s_e, hm, level >= 2 ? hb : 0, EX, odt, m, f32,
+                                           level >= 2 ? round256((size_t)b * m * 4) : 0, stream);
+                if (st != HALO_OK) return st;
+            }
         }
     }
     if (G) {
@@ -339,10 +356,20 @@ halo_status halo_linear_bwd(const halo_linear_desc* desc, const void* E, const i
             st = halo_gemm_i8(EqT, b, Xq, m, 0, n, m, b, s_g, nullptr, G, odt, m, nullptr, 0, stream);
             if (st != HALO_OK) return st;
         } else {
-            st = halo_gemm_i8(EqT, b, Xq, m, 0, n, m, b, nullptr, nullptr, nullptr, odt, 0, acc, m, stream);
+            st = halo_gemm_i8(EqT, b, Xq, m, 0, n, m, b, nullptr, nullptr, nullptr, odt, 0, acc_g, m, stream);
             if (st != HALO_OK) return st;
-            st = halo_dequant_unrotate(acc, m, n, m, s_g, hm, 0, G, odt, m, nullptr, 0, stream);
-            if (st != HALO_OK) return st;
+            if (HALO_BATCH_ROWS && level == 1 && EX) {
+                RowArgs r{};
+                r.in = acc; r.ld_in = m; r.rows = b; r.cols = m; r.pre_scale = s_e; r.out = EX; r.ld_out = m;
+                r.log_block = hm ? ilog2_exact(hm) : 0;
+                r.rows2 = n; r.in2 = acc_g; r.pre_scale2 = s_g; r.out2 = G;
+                if (launch_row_transform(r, IN_I32, odt == HALO_BF16 ? OUT_BF16 : OUT_F32,
+                                         reinterpret_cast<hipStream_t>(stream)) != hipSuccess)
+                    return HALO_EHIP;
+            } else {
+                st = halo_dequant_unrotate(acc_g, m, n, m, s_g, hm, 0, G, odt, m, nullptr, 0, stream);
+                if (st != HALO_OK) return st;
+            }
         }
     }
     return HALO_OK;

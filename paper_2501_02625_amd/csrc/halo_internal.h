@@ -22,6 +22,14 @@ struct RowArgs {
     int64_t ld_out;
     float* out_scale;        // OUT_Q8 only
     int log_block;           // log2 of the Hadamard block, 0 = no rotation
+    // Optional second matrix handled by the same launch (same cols, leading dimensions, fold and block; its own
+    // row count and buffers): rows2 == 0 means none.  Saves one launch ramp/tail when two independent tensors get
+    // the same treatment (X and W in the forward pass, the two accumulators of the backward pass).
+    int64_t rows2;
+    const void* in2;
+    const float* pre_scale2;
+    void* out2;
+    float* out_scale2;
 };
 // Largest row length the row kernels accept.
 constexpr int64_t kMaxRowCols = 32768;

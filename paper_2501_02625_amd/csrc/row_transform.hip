@@ -361,7 +361,7 @@ __device__ __forceinline__ void row_phase2(const RowArgs& a, const RowCtx& x, co
 // XS: number of butterfly stages that span wavefronts (Hadamard block = 2^(LOGSEG+XS) elements = 2^XS segments).
 template <int LOGSEG, int IN, int OUT, int LB, int XS = 0>
 __global__ void __launch_bounds__(LOGSEG >= 11 ? 512 : 1024)
-row_transform_kernel(RowArgs a, int segs, int rows_per_wg, float c_norm) {
+row_transform_kernel(RowArgs a, int segs, int rows_per_wg, float c_norm, unsigned blocks1) {
     constexpr int LOGE = (IN == IN_BF16) ? 3 : 2;
     constexpr int EPL = 1 << LOGE;            // consecutive elements per lane per chunk
     constexpr int VPL = 1 << (LOGSEG - 6);    // values per lane
@@ -379,7 +379,12 @@ row_transform_kernel(RowArgs a, int segs, int rows_per_wg, float c_norm) {
     x.xbuf = s_xbuf;
     x.lane = threadIdx.x & 63;
     x.bperm_addr = (x.lane ^ 32) << 2;
-    x.row = (int64_t)blockIdx.x * rows_per_wg + row_local;
+    unsigned block = blockIdx.x;
+    if (block >= blocks1) {          // the second matrix of a batched launch
+        block -= blocks1;
+        a.in = a.in2; a.pre_scale = a.pre_scale2; a.out = a.out2; a.out_scale = a.out_scale2; a.rows = a.rows2;
+    }
+    x.row = (int64_t)block * rows_per_wg + row_local;
     x.row_ok = x.row < a.rows;
     x.kbase = (int64_t)seg * SEG + (int64_t)x.lane * EPL;
     const bool fast = x.row_ok && ((int64_t)(seg + 1) * SEG <= a.cols);   // uniform over the wavefront
@@ -431,11 +436,12 @@ hipError_t launch_split(const RowArgs& a, hipStream_t s) {
     const int segs = (int)(a.cols >> LOGSEG);
     const int rows_per_wg = segs >= 4 ? 1 : 4 / segs;
     const int threads = 64 * segs * rows_per_wg;
-    const int64_t blocks = (a.rows + rows_per_wg - 1) / rows_per_wg;
+    const int64_t blocks1 = (a.rows + rows_per_wg - 1) / rows_per_wg;
+    const int64_t blocks = blocks1 + (a.rows2 + rows_per_wg - 1) / rows_per_wg;
     const float c_norm = (float)(1.0 / sqrt((double)(int64_t(1) << a.log_block)));
     const size_t lds = (size_t)(threads / 64) * (1 << (LOGSEG - 6)) * 64 * sizeof(float);
     hipLaunchKernelGGL((row_transform_kernel<LOGSEG, IN, OUT, LOGSEG + XS, XS>), dim3((unsigned)blocks), dim3(threads), lds,
-                       s, a, segs, rows_per_wg, c_norm);
+                       s, a, segs, rows_per_wg, c_norm, (unsigned)blocks1);
     return hipGetLastError();
 }
 
@@ -443,17 +449,18 @@ template <int LOGSEG, int IN, int OUT>
 hipError_t launch_one(const RowArgs& a, int segs, hipStream_t s) {
     const int rows_per_wg = segs >= 4 ? 1 : 4 / segs;
     const int threads = 64 * segs * rows_per_wg;
-    const int64_t blocks = (a.rows + rows_per_wg - 1) / rows_per_wg;
+    const int64_t blocks1 = (a.rows + rows_per_wg - 1) / rows_per_wg;
+    const int64_t blocks = blocks1 + (a.rows2 + rows_per_wg - 1) / rows_per_wg;
     const float c_norm = a.log_block > 0 ? (float)(1.0 / sqrt((double)(int64_t(1) << a.log_block))) : 1.0f;
     if (a.log_block == 0)
         hipLaunchKernelGGL((row_transform_kernel<LOGSEG, IN, OUT, 0>), dim3((unsigned)blocks), dim3(threads), 0, s,
-                           a, segs, rows_per_wg, c_norm);
+                           a, segs, rows_per_wg, c_norm, (unsigned)blocks1);
     else if (a.log_block == LOGSEG)
         hipLaunchKernelGGL((row_transform_kernel<LOGSEG, IN, OUT, LOGSEG>), dim3((unsigned)blocks), dim3(threads), 0, s,
-                           a, segs, rows_per_wg, c_norm);
+                           a, segs, rows_per_wg, c_norm, (unsigned)blocks1);
     else
         hipLaunchKernelGGL((row_transform_kernel<LOGSEG, IN, OUT, -1>), dim3((unsigned)blocks), dim3(threads), 0, s,
-                           a, segs, rows_per_wg, c_norm);
+                           a, segs, rows_per_wg, c_norm, (unsigned)blocks1);
     return hipGetLastError();
 }
 
@@ -463,7 +470,7 @@ hipError_t launch_by_seg(const RowArgs& a, hipStream_t s) {
     // for 4096-blocks (5.7 vs 5.2 TB/s at 32768 rows, 12.7 vs 16.0 us at 2048 rows); the quantiser only when whole
     // rows would leave the 1024 SIMDs with fewer than four wavefronts each.
     if (HALO_ROW_SPLIT && (a.log_block == 11 || a.log_block == 12) && a.cols % 1024 == 0 && a.cols <= 16384) {
-        const int64_t wavefronts_unsplit = a.rows * (a.cols >> a.log_block);
+        const int64_t wavefronts_unsplit = (a.rows + a.rows2) * (a.cols >> a.log_block);
         const bool want = IN == IN_I32 ? a.log_block == 12 : wavefronts_unsplit < 4096;
         if (HALO_ROW_SPLIT == 1 || want) {
             return a.log_block == 11 ? launch_split<IN, OUT, 1>(a, s) : launch_split<IN, OUT, 2>(a, s);
@@ -492,7 +499,7 @@ hipError_t launch_by_seg(const RowArgs& a, hipStream_t s) {
 }  // namespace
 
 hipError_t launch_row_transform(const RowArgs& a, InKind in, OutKind out, hipStream_t s) {
-    if (a.rows == 0 || a.cols == 0) return hipSuccess;
+    if ((a.rows == 0 && a.rows2 == 0) || a.cols == 0) return hipSuccess;
     if (a.cols > kMaxRowCols || a.log_block > 12) return hipErrorInvalidValue;
     if (in == IN_BF16 && out == OUT_Q8) return launch_by_seg<IN_BF16, OUT_Q8>(a, s);
     if (in == IN_F32 && out == OUT_Q8) return launch_by_seg<IN_F32, OUT_Q8>(a, s);
