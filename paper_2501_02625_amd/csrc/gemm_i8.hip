@@ -88,9 +88,8 @@ struct GemmCfg {
 // numbers, and walk tiles in groups of GROUP tile-rows so that one XCD's resident tiles share A and B panels in
 // its L2 (measured on an 8192^3 product: 22 % L2 misses with this map, 51 % without the XCD step).
 template <int GROUP>
-__device__ __forceinline__ void tile_of_block(int tiles_m, int tiles_n, int& tile_m, int& tile_n) {
+__device__ __forceinline__ void tile_of_block(int bid, int tiles_m, int tiles_n, int& tile_m, int& tile_n) {
     const int ntiles = tiles_m * tiles_n;
-    const int bid = blockIdx.x;
     const int xcd = bid & 7, q = bid >> 3;
     const int base = ntiles >> 3, rem = ntiles & 7;
     const int pid = xcd * base + (xcd < rem ? xcd : rem) + q;
@@ -309,8 +308,17 @@ __device__ __forceinline__ void wait_vmcnt_lgkm0(int n) {
 // ------------------------------------------------------------------------------------------------ dma main loop
 template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, bool TRANSB, int NS, bool TR = false>
 __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N)
-gemm_i8_dma_kernel(GemmArgs a, int tiles_m, int tiles_n) {
+gemm_i8_dma_kernel(GemmArgs a, int tiles_m, int tiles_n, GemmArgs a2, int tiles_m2, int tiles_n2, unsigned blocks1) {
     using Cfg = GemmCfg<BM, BN, BK, WAVES_M, WAVES_N, TRANSB, NS, TR>;
+    // A second, independent product may ride in the same launch (workgroups from blocks1 on): the tail and the
+    // epilogue of one then overlap the main loop of the other.
+    int bid = blockIdx.x;
+    if (blockIdx.x >= blocks1) {
+        bid -= blocks1;
+        a = a2;
+        tiles_m = tiles_m2;
+        tiles_n = tiles_n2;
+    }
     constexpr bool BOTH_DMA = TRANSB || TR;   // both operands go through the DMA ring
     constexpr int NT = Cfg::NT, CH = Cfg::CH, RPS = Cfg::RPS, TM = Cfg::TM, TN = Cfg::TN;
     constexpr int D = NS - 1;                                     // K steps in flight
@@ -326,7 +334,7 @@ gemm_i8_dma_kernel(GemmArgs a, int tiles_m, int tiles_n) {
     const int lrow = lane & 31, half = lane >> 5;
 
     int tile_m, tile_n;
-    tile_of_block<Cfg::GROUP_M>(tiles_m, tiles_n, tile_m, tile_n);
+    tile_of_block<Cfg::GROUP_M>(bid, tiles_m, tiles_n, tile_m, tile_n);
     const int64_t m0 = (int64_t)tile_m * BM;
     const int64_t n0 = (int64_t)tile_n * BN;
     const int nk = (int)((a.K + BK - 1) / BK);
@@ -523,7 +531,7 @@ gemm_i8_staged_kernel(GemmArgs a, int tiles_m, int tiles_n) {
     const int lrow = lane & 31, half = lane >> 5;
 
     int tile_m, tile_n;
-    tile_of_block<Cfg::GROUP_M>(tiles_m, tiles_n, tile_m, tile_n);
+    tile_of_block<Cfg::GROUP_M>((int)blockIdx.x, tiles_m, tiles_n, tile_m, tile_n);
     const int64_t m0 = (int64_t)tile_m * BM;
     const int64_t n0 = (int64_t)tile_n * BN;
 
@@ -642,6 +650,7 @@ gemm_i8_staged_kernel(GemmArgs a, int tiles_m, int tiles_n) {
 
 // ------------------------------------------------------------------------------------------------ launch
 int g_forced_config = -1;
+int g_pair_backward = 1;         // 0: never put the two backward products into one launch (measurement aid)
 int g_nn_transpose_in_lds = 1;   // 0: transpose the K-strided operand in registers instead (measurement aid)
 
 template <class Kern>
@@ -658,21 +667,42 @@ hipError_t launch_kernel(Kern kern, int lds_bytes, int threads, int bm, int bn, 
     return hipGetLastError();
 }
 
+template <class Kern>
+hipError_t launch_kernel_pair(Kern kern, int lds_bytes, int threads, int bm, int bn, const GemmArgs& a, const GemmArgs* a2,
+                              hipStream_t s, bool* attr_set) {
+    if (!*attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+        if (e != hipSuccess) return e;
+        *attr_set = true;
+    }
+    const int tiles_m = (int)((a.M + bm - 1) / bm), tiles_n = (int)((a.N + bn - 1) / bn);
+    const unsigned blocks1 = (unsigned)(tiles_m * tiles_n);
+    int tiles_m2 = 0, tiles_n2 = 0;
+    if (a2) {
+        tiles_m2 = (int)((a2->M + bm - 1) / bm);
+        tiles_n2 = (int)((a2->N + bn - 1) / bn);
+    }
+    hipLaunchKernelGGL(kern, dim3(blocks1 + (unsigned)(tiles_m2 * tiles_n2)), dim3(threads), lds_bytes, s, a, tiles_m,
+                       tiles_n, a2 ? *a2 : a, tiles_m2, tiles_n2, blocks1);
+    return hipGetLastError();
+}
+
 template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, bool TRANSB, int NS>
-hipError_t launch_dma(const GemmArgs& a, hipStream_t s) {
+hipError_t launch_dma(const GemmArgs& a, hipStream_t s, const GemmArgs* a2 = nullptr) {
     if constexpr (!TRANSB) {
         // K-strided B: the LDS-transposing path needs whole K steps (it cannot zero-fill a K tail)
         if (a.K % BK == 0 && g_nn_transpose_in_lds) {
             using Cfg = GemmCfg<BM, BN, BK, WAVES_M, WAVES_N, false, NS, true>;
             static bool attr_set_tr = false;
-            return launch_kernel(gemm_i8_dma_kernel<BM, BN, BK, WAVES_M, WAVES_N, false, NS, true>, Cfg::LDS_BYTES, Cfg::NT,
-                                 BM, BN, a, s, &attr_set_tr);
+            return launch_kernel_pair(gemm_i8_dma_kernel<BM, BN, BK, WAVES_M, WAVES_N, false, NS, true>, Cfg::LDS_BYTES, Cfg::NT,
+                                 BM, BN, a, a2, s, &attr_set_tr);
         }
     }
     using Cfg = GemmCfg<BM, BN, BK, WAVES_M, WAVES_N, TRANSB, NS>;
     static bool attr_set = false;
-    return launch_kernel(gemm_i8_dma_kernel<BM, BN, BK, WAVES_M, WAVES_N, TRANSB, NS>, Cfg::LDS_BYTES, Cfg::NT, BM, BN,
-                         a, s, &attr_set);
+    return launch_kernel_pair(gemm_i8_dma_kernel<BM, BN, BK, WAVES_M, WAVES_N, TRANSB, NS>, Cfg::LDS_BYTES, Cfg::NT, BM, BN,
+                         a, a2, s, &attr_set);
 }
 
 template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, bool TRANSB>
@@ -731,7 +761,22 @@ hipError_t launch_by_shape(const GemmArgs& a, hipStream_t s) {
 void set_gemm_config(int cfg) {
     // bit 8 of a non-negative value selects the register-transposing variant of the K-strided path
     g_nn_transpose_in_lds = !(cfg >= 0 && (cfg & 0x100));
+    g_pair_backward = !(cfg >= 0 && (cfg & 0x200));
     g_forced_config = cfg >= 0 ? (cfg & 0xFF) : cfg;
+}
+
+// Two K-strided-B products in one launch (the two backward products of the layer).  Falls back to two launches when
+// the shapes do not allow the shared configuration.
+hipError_t launch_gemm_i8_pair(const GemmArgs& a1, const GemmArgs& a2, hipStream_t s) {
+    const bool ok = !a1.transB && !a2.transB && a1.M > 0 && a1.N > 0 && a2.M > 0 && a2.N > 0 && a1.K > 0 && a2.K > 0 &&
+                    a1.K % 64 == 0 && a2.K % 64 == 0 && g_nn_transpose_in_lds && g_pair_backward;
+    if (!ok) {
+        hipError_t e = launch_gemm_i8(a1, s);
+        return e != hipSuccess ? e : launch_gemm_i8(a2, s);
+    }
+    // 256x256 tiles: the E product alone would leave half the CUs idle at 2048 tokens, the pair fills them
+    // (measured on config c2: 183-190 us per step against 197 with 128x128 tiles and 204 with two launches).
+    return launch_dma<256, 256, 64, 2, 4, false, 4>(a1, s, &a2);
 }
 
 hipError_t launch_gemm_i8(const GemmArgs& a, hipStream_t s) {

@@ -320,57 +320,57 @@ halo_status halo_linear_bwd(const halo_linear_desc* desc, const void* E, const i
     int32_t* acc_g = reinterpret_cast<int32_t*>(ws + L.acc_g);
     float* f32 = reinterpret_cast<float*>(ws + L.f32);
 
-    // Levels 0 and 1 quantise the same E twice (per row for E_X, per column for G): one tiling of E does both.
-    const bool dual = EX && G && level <= 1;
-    if (dual) {
+    hipStream_t hs = reinterpret_cast<hipStream_t>(stream);
+    const bool both = EX && G;
+
+    // ---- quantise E: per row for the E product (left-rotated first at level 2), per column (transposed) for G.
+    // Levels 0 and 1 want both from the same E: one tiling of E does both.
+    if (both && level <= 1) {
         st = halo_quant_dual(E, b, n, n, s_w, s_x, Eq, n, s_e, EqT, b, s_g, amax, halo_quant_dual_workspace_bytes(b, n), stream);
         if (st != HALO_OK) return st;
-    }
-    if (EX) {
-        // (E_Y)_Q or (H E_Y)_Q with the saved weight scales folded in
-        if (!dual) {
+    } else {
+        if (EX) {
             st = halo_hadamard_quant(E, HALO_BF16, b, n, n, HALO_QUANT_ROWS, 0, level >= 2 ? hb : 0, s_w, Eq, n, s_e, f32,
                                      level >= 2 ? round256((size_t)b * n * 4) : 0, stream);
             if (st != HALO_OK) return st;
         }
-        if (level == 0) {
-            st = halo_gemm_i8(Eq, n, Wq, m, 0, b, m, n, s_e, nullptr, EX, odt, m, nullptr, 0, stream);
-            if (st != HALO_OK) return st;
-        } else {
-            st = halo_gemm_i8(Eq, n, Wq, m, 0, b, m, n, nullptr, nullptr, nullptr, odt, 0, acc, m, stream);
-            if (st != HALO_OK) return st;
-            if (!(HALO_BATCH_ROWS && level == 1 && G)) {      // at level 1 with both products, one launch un-rotates both accumulators below
-                st = halo_dequant_unrotate(acc, m, b, m, s_e, hm, level >= 2 ? hb : 0, EX, odt, m, f32,
-                                           level >= 2 ? round256((size_t)b * m * 4) : 0, stream);
-                if (st != HALO_OK) return st;
-            }
-        }
-    }
-    if (G) {
-        if (!dual) {
+        if (G) {
             st = halo_hadamard_quant(E, HALO_BF16, b, n, n, HALO_QUANT_COLS_T, 0, 0, s_x, EqT, b, s_g, amax,
                                      round256((size_t)n * 4), stream);
             if (st != HALO_OK) return st;
         }
-        if (level == 0) {
-            st = halo_gemm_i8(EqT, b, Xq, m, 0, n, m, b, s_g, nullptr, G, odt, m, nullptr, 0, stream);
-            if (st != HALO_OK) return st;
-        } else {
-            st = halo_gemm_i8(EqT, b, Xq, m, 0, n, m, b, nullptr, nullptr, nullptr, odt, 0, acc_g, m, stream);
-            if (st != HALO_OK) return st;
-            if (HALO_BATCH_ROWS && level == 1 && EX) {
-                RowArgs r{};
-                r.in = acc; r.ld_in = m; r.rows = b; r.cols = m; r.pre_scale = s_e; r.out = EX; r.ld_out = m;
-                r.log_block = hm ? ilog2_exact(hm) : 0;
-                r.rows2 = n; r.in2 = acc_g; r.pre_scale2 = s_g; r.out2 = G;
-                if (launch_row_transform(r, IN_I32, odt == HALO_BF16 ? OUT_BF16 : OUT_F32,
-                                         reinterpret_cast<hipStream_t>(stream)) != hipSuccess)
-                    return HALO_EHIP;
-            } else {
-                st = halo_dequant_unrotate(acc_g, m, n, m, s_g, hm, 0, G, odt, m, nullptr, 0, stream);
-                if (st != HALO_OK) return st;
-            }
-        }
+    }
+
+    // ---- the two products on the saved codes.  Level 0 scales and stores the result in the epilogue; levels 1, 2
+    // leave int32 accumulators for the un-rotation.  When both are wanted they share one launch.
+    GemmArgs gx{Eq, n, Wq, m, 0, b, m, n, level == 0 ? s_e : nullptr, nullptr, level == 0 ? EX : nullptr,
+                odt == HALO_F32 ? 1 : 0, m, level == 0 ? nullptr : acc, m};
+    GemmArgs gg{EqT, b, Xq, m, 0, n, m, b, level == 0 ? s_g : nullptr, nullptr, level == 0 ? G : nullptr,
+                odt == HALO_F32 ? 1 : 0, m, level == 0 ? nullptr : acc_g, m};
+    hipError_t he = hipSuccess;
+    if (both) he = launch_gemm_i8_pair(gx, gg, hs);
+    else if (EX) he = launch_gemm_i8(gx, hs);
+    else he = launch_gemm_i8(gg, hs);
+    if (he != hipSuccess) return HALO_EHIP;
+    if (level == 0) return HALO_OK;
+
+    // ---- dequantise and un-rotate
+    if (HALO_BATCH_ROWS && both && level == 1) {
+        RowArgs r{};
+        r.in = acc; r.ld_in = m; r.rows = b; r.cols = m; r.pre_scale = s_e; r.out = EX; r.ld_out = m;
+        r.log_block = hm ? ilog2_exact(hm) : 0;
+        r.rows2 = n; r.in2 = acc_g; r.pre_scale2 = s_g; r.out2 = G;
+        if (launch_row_transform(r, IN_I32, odt == HALO_BF16 ? OUT_BF16 : OUT_F32, hs) != hipSuccess) return HALO_EHIP;
+        return HALO_OK;
+    }
+    if (EX) {
+        st = halo_dequant_unrotate(acc, m, b, m, s_e, hm, level >= 2 ? hb : 0, EX, odt, m, f32,
+                                   level >= 2 ? round256((size_t)b * m * 4) : 0, stream);
+        if (st != HALO_OK) return st;
+    }
+    if (G) {
+        st = halo_dequant_unrotate(acc_g, m, n, m, s_g, hm, 0, G, odt, m, nullptr, 0, stream);
+        if (st != HALO_OK) return st;
     }
     return HALO_OK;
 }

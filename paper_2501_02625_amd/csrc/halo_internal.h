@@ -100,6 +100,7 @@ struct GemmArgs {
     int64_t ld_acc;
 };
 hipError_t launch_gemm_i8(const GemmArgs& a, hipStream_t s);
+hipError_t launch_gemm_i8_pair(const GemmArgs& a1, const GemmArgs& a2, hipStream_t s);
 // Tuning hook: force one macro-tile configuration (-1 = choose by shape).
 void set_gemm_config(int cfg);
 
