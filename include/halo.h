@@ -130,6 +130,23 @@ halo_status halo_gemm_i8(const int8_t* A, int64_t lda, const int8_t* B, int64_t 
                          const float* col_scale, void* C, halo_dtype c_dt, int64_t ldc,
                          int32_t* acc_out, int64_t ld_acc, void* stream);
 
+/* Two independent products in one launch: same semantics and bit-identical results as two halo_gemm_i8 calls (in
+ * either order).  halo_linear_bwd uses it for E_X = E W and G = E^T X, where the tail and the epilogue of one product
+ * overlap the main loop of the other and the smaller one cannot leave compute units idle.  Products with a
+ * K-contiguous B, a K that is not a multiple of 64, or an empty shape are simply run one after the other.
+ * Every field of halo_gemm_desc means what the argument of the same name means in halo_gemm_i8. */
+typedef struct halo_gemm_desc {
+    const int8_t* A; int64_t lda;
+    const int8_t* B; int64_t ldb;
+    int32_t transB;
+    int64_t M, N, K;
+    const float* row_scale; const float* col_scale;
+    void* C; int32_t c_dt /* halo_dtype */; int64_t ldc;
+    int32_t* acc_out; int64_t ld_acc;
+} halo_gemm_desc;
+
+halo_status halo_gemm_i8_pair(const halo_gemm_desc* g1, const halo_gemm_desc* g2, void* stream);
+
 /* Tuning hook for halo_gemm_i8 (process-wide, not thread-safe): config >= 0 forces one macro-tile /
  * pipeline configuration for every following GEMM, -1 (the default) lets the library choose by shape.
  * Configurations differ in speed only; results are identical.  Unknown values make halo_gemm_i8 return

@@ -24,7 +24,7 @@ EXPORTED_SYMBOLS = (
     "halo_status_string", "halo_version",
     "halo_hadamard_quant_workspace_bytes", "halo_hadamard_quant",
     "halo_quant_dual_workspace_bytes", "halo_quant_dual",
-    "halo_gemm_i8", "halo_gemm_i8_set_config",
+    "halo_gemm_i8", "halo_gemm_i8_pair", "halo_gemm_i8_set_config",
     "halo_dequant_unrotate_workspace_bytes", "halo_dequant_unrotate",
     "halo_linear_workspace_bytes", "halo_linear_fwd", "halo_linear_bwd",
 )
@@ -34,6 +34,14 @@ class HaloError(RuntimeError):
     def __init__(self, status: int, where: str):
         self.status = status
         super().__init__("%s failed: %s (status %d)" % (where, status_string(status), status))
+
+
+class GemmDesc(ctypes.Structure):
+    _fields_ = [("A", ctypes.c_void_p), ("lda", ctypes.c_int64), ("B", ctypes.c_void_p), ("ldb", ctypes.c_int64),
+                ("transB", ctypes.c_int32), ("M", ctypes.c_int64), ("N", ctypes.c_int64), ("K", ctypes.c_int64),
+                ("row_scale", ctypes.c_void_p), ("col_scale", ctypes.c_void_p), ("C", ctypes.c_void_p),
+                ("c_dt", ctypes.c_int32), ("ldc", ctypes.c_int64), ("acc_out", ctypes.c_void_p),
+                ("ld_acc", ctypes.c_int64)]
 
 
 class LinearDesc(ctypes.Structure):
@@ -72,6 +80,8 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.halo_quant_dual.argtypes = [vp, i64, i64, i64, vp, vp, vp, i64, vp, vp, i64, vp, vp, sz, vp]
     lib.halo_gemm_i8.restype = c.c_int
     lib.halo_gemm_i8.argtypes = [vp, i64, vp, i64, c.c_int, i64, i64, i64, vp, vp, vp, c.c_int, i64, vp, i64, vp]
+    lib.halo_gemm_i8_pair.restype = c.c_int
+    lib.halo_gemm_i8_pair.argtypes = [c.POINTER(GemmDesc), c.POINTER(GemmDesc), vp]
     lib.halo_gemm_i8_set_config.restype = None
     lib.halo_gemm_i8_set_config.argtypes = [c.c_int]
     lib.halo_dequant_unrotate_workspace_bytes.restype = sz
@@ -207,6 +217,25 @@ def halo_gemm_i8(a: torch.Tensor, b: torch.Tensor, *, trans_b: bool, row_scale: 
                           (acc_out.stride(0) if M else N) if acc_out is not None else 0, _stream())
     _check(st, "halo_gemm_i8")
     return out, acc_out
+
+
+def gemm_desc(a: torch.Tensor, b: torch.Tensor, *, trans_b: bool, row_scale: Optional[torch.Tensor] = None,
+              col_scale: Optional[torch.Tensor] = None, out: Optional[torch.Tensor] = None,
+              acc_out: Optional[torch.Tensor] = None) -> GemmDesc:
+    """Marshal one product for halo_gemm_i8_pair (the caller keeps the tensors alive)."""
+    _need_cuda(a, b, row_scale, col_scale, out, acc_out)
+    M, K = a.shape
+    N = b.shape[0] if trans_b else b.shape[1]
+    dp = lambda t: None if t is None else t.data_ptr()
+    return GemmDesc(dp(a), a.stride(0), dp(b), b.stride(0), 1 if trans_b else 0, M, N, K, dp(row_scale), dp(col_scale),
+                    dp(out), _dt(out.dtype) if out is not None else HALO_F32, out.stride(0) if out is not None else 0,
+                    dp(acc_out), acc_out.stride(0) if acc_out is not None else 0)
+
+
+def halo_gemm_i8_pair(g1: GemmDesc, g2: GemmDesc) -> None:
+    """Two independent products in one launch."""
+    st = load_library().halo_gemm_i8_pair(ctypes.byref(g1), ctypes.byref(g2), _stream())
+    _check(st, "halo_gemm_i8_pair")
 
 
 def halo_gemm_i8_set_config(config: int) -> None:

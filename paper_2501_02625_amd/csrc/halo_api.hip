@@ -183,32 +183,58 @@ halo_status halo_quant_dual(const void* in, int64_t rows, int64_t cols, int64_t 
 }
 
 // ------------------------------------------------------------------------------------------------
+// Argument check shared by halo_gemm_i8 and halo_gemm_i8_pair.  *skip is set when the product is empty (a no-op).
+static halo_status check_gemm(const halo_gemm_desc* d, GemmArgs* out, bool* skip) {
+    *skip = false;
+    if (d->M < 0 || d->N < 0 || d->K < 0) return HALO_EINVAL;
+    if (d->c_dt != HALO_BF16 && d->c_dt != HALO_F32) return HALO_EINVAL;
+    if (d->M == 0 || d->N == 0) { *skip = true; return HALO_OK; }
+    if (!d->C && !d->acc_out) return HALO_EINVAL;
+    if (d->K > 0 && (!d->A || !d->B)) return HALO_EINVAL;
+    if (d->M > kMaxDim || d->N > kMaxDim || d->K > kMaxDim) return HALO_EUNSUPPORTED;
+    if (d->K % 16) return HALO_ESHAPE;
+    if (127ll * 127ll * d->K >= (1ll << 31)) return HALO_ESHAPE;
+    if (d->K > 0) {
+        if (d->lda < d->K || d->ldb < (d->transB ? d->K : d->N)) return HALO_ESHAPE;
+        if (!aligned16(d->A) || !aligned16(d->B) || d->lda % 16 || d->ldb % 16) return HALO_EALIGN;
+    }
+    if (d->C) {
+        if (d->ldc < d->N) return HALO_ESHAPE;
+        if (!aligned16(d->C) || (d->ldc * (d->c_dt == HALO_BF16 ? 2 : 4)) % 16) return HALO_EALIGN;
+    }
+    if (d->acc_out) {
+        if (d->ld_acc < d->N) return HALO_ESHAPE;
+        if (!aligned16(d->acc_out) || (d->ld_acc * 4) % 16) return HALO_EALIGN;
+    }
+    *out = GemmArgs{d->A, d->lda, d->B, d->ldb, d->transB ? 1 : 0, d->M, d->N, d->K, d->row_scale, d->col_scale, d->C,
+                    d->c_dt == HALO_F32 ? 1 : 0, d->ldc, d->acc_out, d->ld_acc};
+    return HALO_OK;
+}
+
 halo_status halo_gemm_i8(const int8_t* A, int64_t lda, const int8_t* B, int64_t ldb, int transB, int64_t M,
                          int64_t N, int64_t K, const float* row_scale, const float* col_scale, void* C,
                          halo_dtype c_dt, int64_t ldc, int32_t* acc_out, int64_t ld_acc, void* stream) {
-    if (M < 0 || N < 0 || K < 0) return HALO_EINVAL;
-    if (c_dt != HALO_BF16 && c_dt != HALO_F32) return HALO_EINVAL;
-    if (M == 0 || N == 0) return HALO_OK;
-    if (!C && !acc_out) return HALO_EINVAL;
-    if (K > 0 && (!A || !B)) return HALO_EINVAL;
-    if (M > kMaxDim || N > kMaxDim || K > kMaxDim) return HALO_EUNSUPPORTED;
-    if (K % 16) return HALO_ESHAPE;
-    if (127ll * 127ll * K >= (1ll << 31)) return HALO_ESHAPE;
-    if (K > 0) {
-        if (lda < K || ldb < (transB ? K : N)) return HALO_ESHAPE;
-        if (!aligned16(A) || !aligned16(B) || lda % 16 || ldb % 16) return HALO_EALIGN;
-    }
-    if (C) {
-        if (ldc < N) return HALO_ESHAPE;
-        if (!aligned16(C) || (ldc * (c_dt == HALO_BF16 ? 2 : 4)) % 16) return HALO_EALIGN;
-    }
-    if (acc_out) {
-        if (ld_acc < N) return HALO_ESHAPE;
-        if (!aligned16(acc_out) || (ld_acc * 4) % 16) return HALO_EALIGN;
-    }
-    GemmArgs g{A, lda, B, ldb, transB ? 1 : 0, M, N, K, row_scale, col_scale, C, c_dt == HALO_F32 ? 1 : 0, ldc,
-               acc_out, ld_acc};
+    const halo_gemm_desc d{A, lda, B, ldb, transB, M, N, K, row_scale, col_scale, C, (int32_t)c_dt, ldc, acc_out, ld_acc};
+    GemmArgs g;
+    bool skip;
+    const halo_status st = check_gemm(&d, &g, &skip);
+    if (st != HALO_OK || skip) return st;
     return from_hip(launch_gemm_i8(g, reinterpret_cast<hipStream_t>(stream)));
+}
+
+halo_status halo_gemm_i8_pair(const halo_gemm_desc* g1, const halo_gemm_desc* g2, void* stream) {
+    if (!g1 || !g2) return HALO_EINVAL;
+    GemmArgs a1, a2;
+    bool skip1, skip2;
+    halo_status st = check_gemm(g1, &a1, &skip1);
+    if (st != HALO_OK) return st;
+    st = check_gemm(g2, &a2, &skip2);
+    if (st != HALO_OK) return st;
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    if (skip1 && skip2) return HALO_OK;
+    if (skip1) return from_hip(launch_gemm_i8(a2, s));
+    if (skip2) return from_hip(launch_gemm_i8(a1, s));
+    return from_hip(launch_gemm_i8_pair(a1, a2, s));
 }
 
 // ------------------------------------------------------------------------------------------------

@@ -102,6 +102,19 @@ def test_gemm_argument_errors(lib):
     assert f(None, 0, None, 0, 1, 0, 32, 64, None, None, None, 1, 32, None, 0, None) == binding.HALO_OK
 
 
+def test_gemm_pair_argument_errors(lib):
+    A, B, C = 0x1000, 0x2000, 0x3000
+    good = binding.GemmDesc(A, 64, B, 64, 0, 32, 64, 64, None, None, C, binding.HALO_F32, 64, None, 0)
+    bad_k = binding.GemmDesc(A, 64, B, 64, 0, 32, 64, 40, None, None, C, binding.HALO_F32, 64, None, 0)
+    no_out = binding.GemmDesc(A, 64, B, 64, 0, 32, 64, 64, None, None, None, binding.HALO_F32, 64, None, 0)
+    empty = binding.GemmDesc(None, 0, None, 0, 0, 0, 64, 64, None, None, None, binding.HALO_F32, 0, None, 0)
+    f = lib.halo_gemm_i8_pair
+    assert f(None, ctypes.byref(good), None) == binding.HALO_EINVAL
+    assert f(ctypes.byref(good), ctypes.byref(bad_k), None) == binding.HALO_ESHAPE
+    assert f(ctypes.byref(no_out), ctypes.byref(good), None) == binding.HALO_EINVAL
+    assert f(ctypes.byref(empty), ctypes.byref(empty), None) == binding.HALO_OK
+
+
 def test_linear_desc_errors_and_workspace(lib):
     d = binding.make_desc(2048, 4096, 4096, 1)
     ws1 = binding.halo_linear_workspace_bytes(d)

@@ -109,3 +109,31 @@ def test_gemm_k_zero_writes_zeros_and_empty_is_noop():
     b = torch.empty((16, 64), dtype=torch.int8, device=gu.DEV)
     c, _ = binding.halo_gemm_i8(a, b, trans_b=True)
     assert c.shape == (0, 16)
+
+
+def test_gemm_pair_matches_two_single_launches():
+    """Both backward products in one launch give the same bits as two launches (config c2's shapes scaled down,
+    ragged edges, one scaled bf16 output and one raw accumulator output)."""
+    rng = np.random.default_rng(9)
+    b, m, n = 384, 512, 640
+    Eq = rand_codes(rng, (b, n)); Wq = rand_codes(rng, (n, m)); EqT = rand_codes(rng, (n, b)); Xq = rand_codes(rng, (b, m))
+    s_e = (np.abs(rng.standard_normal(b)) * 1e-3 + 1e-5).astype(np.float32)
+    dEq, dWq, dEqT, dXq = map(gu.to_dev, (Eq, Wq, EqT, Xq))
+    ex = torch.zeros((b, m), dtype=torch.bfloat16, device=gu.DEV)
+    acc_g = torch.zeros((n, m), dtype=torch.int32, device=gu.DEV)
+    g1 = binding.gemm_desc(dEq, dWq, trans_b=False, row_scale=gu.to_dev(s_e), out=ex)
+    g2 = binding.gemm_desc(dEqT, dXq, trans_b=False, acc_out=acc_g)
+    binding.halo_gemm_i8_pair(g1, g2)
+    want_ex = orc.dequantize(orc.gemm_codes(Eq, Wq), s_e)
+    gu.assert_bf16_within_one_ulp(ex, want_ex, "paired E_X")
+    gu.assert_codes_equal(acc_g, orc.gemm_codes(EqT, Xq), "paired G accumulators")
+    ex1, _ = binding.halo_gemm_i8(dEq, dWq, trans_b=False, row_scale=gu.to_dev(s_e), out_dtype=torch.bfloat16)
+    assert torch.equal(ex.view(torch.int16), ex1.contiguous().view(torch.int16))
+    # a pair the shared configuration cannot take (K-contiguous B, ragged K) still works
+    a = rand_codes(rng, (70, 80)); bb = rand_codes(rng, (50, 80))
+    acc1 = torch.zeros((70, 52), dtype=torch.int32, device=gu.DEV)[:, :50]
+    acc2 = torch.zeros((n, m), dtype=torch.int32, device=gu.DEV)
+    binding.halo_gemm_i8_pair(binding.gemm_desc(gu.to_dev(a), gu.to_dev(bb), trans_b=True, acc_out=acc1),
+                              binding.gemm_desc(dEqT, dXq, trans_b=False, acc_out=acc2))
+    gu.assert_codes_equal(acc1, orc.gemm_codes(a, bb.T), "fallback pair, first")
+    gu.assert_codes_equal(acc2, orc.gemm_codes(EqT, Xq), "fallback pair, second")
