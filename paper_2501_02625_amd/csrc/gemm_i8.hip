@@ -2,21 +2,25 @@
 // dequantisation epilogue:  C = diag(row_scale) * (A * op(B)) * diag(col_scale).
 //
 //   A  [M x K]  K contiguous.
-//   B  transB:  [N x K], K contiguous  -> both operands stream 16-byte K-chunks straight into LDS.
-//      !transB: [K x N], K strided     -> 4(k) x 4(n) byte blocks are transposed in registers with v_perm_b32
-//               on their way to LDS, so the saved (WH)_Q / (XH)_Q codes are reused by the backward
-//               products without a transposed copy in HBM.
+//   B  transB:  [N x K], K contiguous.
+//      !transB: [K x N], K strided: the saved (WH)_Q / (XH)_Q codes are reused by the backward products as they are,
+//               without a transposed copy in HBM.
 //
 // Workgroup = WAVES_M x WAVES_N wavefronts, macro tile BM x BN, K step BK bytes.  Each wavefront owns a
 // (BM/WAVES_M) x (BN/WAVES_N) sub-tile as a grid of 32x32 MFMA tiles.
 //
-// Two main loops:
-//   * "dma" (the fast path): an NS-deep ring of LDS stages filled by global_load_lds_dwordx4 (global memory ->
-//     LDS without passing through registers), NS-1 K steps in flight, one s_barrier per K step and explicit
-//     s_waitcnt vmcnt(n) so that only the oldest stage is waited for.  The K-strided B operand cannot use it
-//     (its bytes must be transposed), so it is prefetched one K step ahead in registers.
-//   * "staged": two LDS stages, next K step prefetched in registers.  Handles a K that is not a multiple of BK
-//     for the K-contiguous/K-contiguous case, where the DMA path cannot zero-fill the K tail.
+// Main loops:
+//   * "dma", all operands (the fast path): an NS-deep ring of LDS stages filled by global_load_lds_dwordx4 (global
+//     memory -> LDS without passing through registers).  Exactly one K step is issued per iteration, sliced between
+//     the MFMA sub-steps, so the s_waitcnt vmcnt(n) that waits for the oldest stage only is a constant; one s_barrier
+//     per K step.  A K-contiguous operand is stored [row][BK bytes]; a K-strided B is stored as it lies in memory
+//     (K-major rows of BN bytes) and transposed by the LDS read itself, ds_read_b64_tr_b8: a group of 16 lanes reads an
+//     8(k) x 16(n) byte block, lane i supplying the address of row i/2, half i%2, and receiving column i.
+//   * "dma" for A with a register-transposed B (4x4 byte blocks through v_perm_b32): K-strided B whose K is not a
+//     multiple of the K step (the DMA cannot zero-fill a K tail).
+//   * "staged": two LDS stages, next K step prefetched in registers; K-contiguous B with a ragged K.
+// A launch may carry two independent products (halo_gemm_i8_pair): workgroups past the first product's tile count
+// take the second argument block.
 //
 // MFMA operand layout (32x32x32 i8): lane l supplies 16 consecutive K-bytes of row (l % 32), taken from K
 // offset 16*(l / 32) of the 32-byte K step, for A and for B alike; since both operands use the same
@@ -24,12 +28,11 @@
 // sums them in.  Accumulator layout: lane l holds column (l % 32) and rows 8*(r/4) + 4*(l/32) + (r%4),
 // r = 0..15.
 //
-// LDS layouts.  K-contiguous operands: [row][BK bytes], the 16-byte chunk index XOR-swizzled with the row
-// so that the 16 rows read by one quarter-wave ds_read_b128 fall in 16 different bank groups (measured:
-// zero LDS bank conflicts); a DMA lane writes LDS slot (wave slot base + lane), so the swizzle is applied to
-// the global address it fetches.  K-strided B: dwords of four consecutive k, laid out [k/4][n] with a row
-// pitch of BN+8 dwords; the transposing writes are contiguous 16-byte stores and the operand reads are
-// conflict-free ds_read_b32.
+// LDS layouts.  K-contiguous operands: the 16-byte chunk index is XOR-swizzled with the row so that the 16 rows read
+// by one quarter-wave ds_read_b128 fall in 16 different bank groups (measured: zero LDS bank conflicts); a DMA lane
+// writes LDS slot (wave slot base + lane), so the swizzle is applied to the global address it fetches.  K-major B:
+// chunks XOR-swizzled by 2*(row % 8) (BN = 256) so that the two lane groups of one transposing read stay on even and
+// odd chunks.  Register-transposed B: dwords of four consecutive k, laid out [k/4][n] with a row pitch of BN+8 dwords.
 #include "halo_internal.h"
 
 namespace halo {
