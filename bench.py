@@ -35,7 +35,7 @@ def parse():
     p.add_argument("--kernel-iters", type=int, default=50, help="launches per kernel for the per-kernel timings")
     p.add_argument("--pmc-target", default="",
                    help="run ONE kernel family --steps times and exit (for rocprofv3 --pmc runs): gemm_fwd, gemm_ex, "
-                        "gemm_g, rowquant_x, rowquant_w, quant_dual, unrotate_ex, unrotate_g, copy")
+                        "gemm_g, gemm_pair, rowquant_x, rowquant_w, quant_dual, unrotate_ex, unrotate_g, copy")
     p.add_argument("--step-only", action="store_true",
                    help="time the step loop only (no per-kernel loops, no oracle): what a kernel-trace profile of the step needs")
     return p.parse_args()
@@ -116,6 +116,8 @@ def main():
             "gemm_fwd": lambda: binding.halo_gemm_i8(state.Xq, state.Wq, trans_b=True, row_scale=state.s_x, col_scale=state.s_w, out=Y),
             "gemm_ex": lambda: binding.halo_gemm_i8(Eq_, state.Wq, trans_b=False, out_dtype=None, acc_out=acc1),
             "gemm_g": lambda: binding.halo_gemm_i8(EqT_, state.Xq, trans_b=False, out_dtype=None, acc_out=acc2),
+            "gemm_pair": lambda: binding.halo_gemm_i8_pair(binding.gemm_desc(Eq_, state.Wq, trans_b=False, acc_out=acc1),
+                                                           binding.gemm_desc(EqT_, state.Xq, trans_b=False, acc_out=acc2)),
             "rowquant_x": lambda: binding.halo_hadamard_quant(X, had_block=hm, out_q=state.Xq, out_scale=state.s_x),
             "rowquant_w": lambda: binding.halo_hadamard_quant(W, had_block=hm, out_q=state.Wq, out_scale=state.s_w),
             "quant_dual": lambda: binding.halo_quant_dual(E, fold_cols=state.s_w, fold_rows=state.s_x, out_q=qd[0], row_scale=qd[1],
