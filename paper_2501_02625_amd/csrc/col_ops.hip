@@ -2,7 +2,8 @@
 //   * left-hand Walsh-Hadamard rotation  h'(A) = H^T A  over blocks of rows, done directly on strided data
 //     (no transposes): each lane keeps 2^LOGR rows of one or two columns in registers, so all butterflies of
 //     a pass are register-to-register and the memory accesses stay coalesced along the rows;
-//   * the column-wise absmax INT8 quantiser with transposed output, (E^T)_Q.
+//   * the column-wise absmax INT8 quantiser with transposed output, (E^T)_Q;
+//   * the dual quantiser: row-wise codes (E_Y)_Q and transposed column-wise codes (E_Y^T)_Q from one tiling of E.
 #pragma clang fp contract(off)
 
 #include "halo_internal.h"
