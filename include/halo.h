@@ -130,11 +130,20 @@ halo_status halo_gemm_i8(const int8_t* A, int64_t lda, const int8_t* B, int64_t 
                          const float* col_scale, void* C, halo_dtype c_dt, int64_t ldc,
                          int32_t* acc_out, int64_t ld_acc, void* stream);
 
-/* Two independent products in one launch: same semantics and bit-identical results as two halo_gemm_i8 calls (in
- * either order).  halo_linear_bwd uses it for E_X = E W and G = E^T X, where the tail and the epilogue of one product
- * overlap the main loop of the other and the smaller one cannot leave compute units idle.  Products with a
- * K-contiguous B, a K that is not a multiple of 64, or an empty shape are simply run one after the other.
- * Every field of halo_gemm_desc means what the argument of the same name means in halo_gemm_i8. */
+/* Tile configurations of the INT8 GEMM: macro tile M x N x K-step (bytes), wavefronts per workgroup.  They differ in
+ * speed only, the results are identical.  HALO_GEMM_AUTO lets the library choose by shape.  A configuration whose
+ * K step does not divide K is refused with HALO_ESHAPE (the staged one takes any K that is a multiple of 16). */
+typedef enum {
+    HALO_GEMM_AUTO = -1,
+    HALO_GEMM_256x256x64 = 0,        /* 8 wavefronts, four-stage global->LDS ring                  */
+    HALO_GEMM_256x256x128 = 1,       /* 8 wavefronts, two-stage ring                               */
+    HALO_GEMM_256x128x128 = 2,       /* 8 wavefronts, three-stage ring                             */
+    HALO_GEMM_128x128x64 = 3,        /* 4 wavefronts, four-stage ring                              */
+    HALO_GEMM_STAGED_128x128x64 = 4  /* 4 wavefronts, register-staged, zero-fills a ragged K       */
+} halo_gemm_config;
+
+/* One product described by a struct: every field means what the argument of the same name means in halo_gemm_i8;
+ * `config` is a halo_gemm_config. */
 typedef struct halo_gemm_desc {
     const int8_t* A; int64_t lda;
     const int8_t* B; int64_t ldb;
@@ -143,15 +152,26 @@ typedef struct halo_gemm_desc {
     const float* row_scale; const float* col_scale;
     void* C; int32_t c_dt /* halo_dtype */; int64_t ldc;
     int32_t* acc_out; int64_t ld_acc;
+    int32_t config /* halo_gemm_config */;
 } halo_gemm_desc;
 
+/* halo_gemm_i8 with the tile configuration under the caller's control (measurements, tests of every configuration). */
+halo_status halo_gemm_i8_desc(const halo_gemm_desc* g, void* stream);
+
+/* Two independent products in one launch: same semantics and bit-identical results as two halo_gemm_i8_desc calls (in
+ * either order).  halo_linear_bwd uses it for E_X = E W and G = E^T X, where the tail and the epilogue of one product
+ * overlap the main loop of the other and the smaller one cannot leave compute units idle.  Products with a
+ * K-contiguous B, a K that is not a multiple of 64, different configurations, a configuration other than AUTO,
+ * 256x256x64 or 128x128x64, or an empty shape are simply run one after the other. */
 halo_status halo_gemm_i8_pair(const halo_gemm_desc* g1, const halo_gemm_desc* g2, void* stream);
 
-/* Tuning hook for halo_gemm_i8 (process-wide, not thread-safe): config >= 0 forces one macro-tile /
- * pipeline configuration for every following GEMM, -1 (the default) lets the library choose by shape.
- * Configurations differ in speed only; results are identical.  Unknown values make halo_gemm_i8 return
- * HALO_EHIP. */
-void halo_gemm_i8_set_config(int config);
+/* Measurement aid: the INT8 MFMA rate this machine sustains on given operand bytes.  256 workgroups of 8 wavefronts
+ * each issue iters x 16 v_mfma_i32_32x32x32_i8 on the 4096 operand bytes at `operands` (device, 16-byte aligned) with
+ * nothing else in the loop: 256 * 8 * iters * 16 * 65536 integer operations.  The rate depends on the operand data
+ * (the clock drops as more multiplier bits toggle), which is why the throughput of halo_gemm_i8 is reported against
+ * this figure next to the published peak (Section 4, "Speedup Analysis", measures against an ideal layer likewise).
+ * `sink` is an optional int32 the kernel may write (it keeps the loop from being optimised away). */
+halo_status halo_mfma_i8_probe(const int8_t* operands, int32_t iters, int32_t* sink, void* stream);
 
 /* ---------------------------------------------------------------------------------------------
  * halo_dequant_unrotate: the tail of both backward products.   (Table "HALO levels": the trailing H^T

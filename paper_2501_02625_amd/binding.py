@@ -19,12 +19,14 @@ HALO_OK = 0
 HALO_EINVAL, HALO_ESHAPE, HALO_EALIGN, HALO_EWORKSPACE, HALO_EUNSUPPORTED, HALO_EHIP = 1, 2, 3, 4, 5, 6
 HALO_BF16, HALO_F32 = 0, 1
 HALO_QUANT_ROWS, HALO_QUANT_COLS_T = 0, 1
+HALO_GEMM_AUTO = -1
+HALO_GEMM_CONFIGS = {"256x256x64": 0, "256x256x128": 1, "256x128x128": 2, "128x128x64": 3, "staged_128x128x64": 4}
 
 EXPORTED_SYMBOLS = (
     "halo_status_string", "halo_version",
     "halo_hadamard_quant_workspace_bytes", "halo_hadamard_quant",
     "halo_quant_dual_workspace_bytes", "halo_quant_dual",
-    "halo_gemm_i8", "halo_gemm_i8_pair", "halo_gemm_i8_set_config",
+    "halo_gemm_i8", "halo_gemm_i8_desc", "halo_gemm_i8_pair", "halo_mfma_i8_probe",
     "halo_dequant_unrotate_workspace_bytes", "halo_dequant_unrotate",
     "halo_linear_workspace_bytes", "halo_linear_fwd", "halo_linear_bwd",
 )
@@ -41,7 +43,7 @@ class GemmDesc(ctypes.Structure):
                 ("transB", ctypes.c_int32), ("M", ctypes.c_int64), ("N", ctypes.c_int64), ("K", ctypes.c_int64),
                 ("row_scale", ctypes.c_void_p), ("col_scale", ctypes.c_void_p), ("C", ctypes.c_void_p),
                 ("c_dt", ctypes.c_int32), ("ldc", ctypes.c_int64), ("acc_out", ctypes.c_void_p),
-                ("ld_acc", ctypes.c_int64)]
+                ("ld_acc", ctypes.c_int64), ("config", ctypes.c_int32)]
 
 
 class LinearDesc(ctypes.Structure):
@@ -82,8 +84,10 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.halo_gemm_i8.argtypes = [vp, i64, vp, i64, c.c_int, i64, i64, i64, vp, vp, vp, c.c_int, i64, vp, i64, vp]
     lib.halo_gemm_i8_pair.restype = c.c_int
     lib.halo_gemm_i8_pair.argtypes = [c.POINTER(GemmDesc), c.POINTER(GemmDesc), vp]
-    lib.halo_gemm_i8_set_config.restype = None
-    lib.halo_gemm_i8_set_config.argtypes = [c.c_int]
+    lib.halo_gemm_i8_desc.restype = c.c_int
+    lib.halo_gemm_i8_desc.argtypes = [c.POINTER(GemmDesc), vp]
+    lib.halo_mfma_i8_probe.restype = c.c_int
+    lib.halo_mfma_i8_probe.argtypes = [vp, i32, vp, vp]
     lib.halo_dequant_unrotate_workspace_bytes.restype = sz
     lib.halo_dequant_unrotate_workspace_bytes.argtypes = [i64, i64, i32]
     lib.halo_dequant_unrotate.restype = c.c_int
@@ -221,15 +225,15 @@ def halo_gemm_i8(a: torch.Tensor, b: torch.Tensor, *, trans_b: bool, row_scale: 
 
 def gemm_desc(a: torch.Tensor, b: torch.Tensor, *, trans_b: bool, row_scale: Optional[torch.Tensor] = None,
               col_scale: Optional[torch.Tensor] = None, out: Optional[torch.Tensor] = None,
-              acc_out: Optional[torch.Tensor] = None) -> GemmDesc:
-    """Marshal one product for halo_gemm_i8_pair (the caller keeps the tensors alive)."""
+              acc_out: Optional[torch.Tensor] = None, config: int = HALO_GEMM_AUTO) -> GemmDesc:
+    """Marshal one product for halo_gemm_i8_desc / halo_gemm_i8_pair (the caller keeps the tensors alive)."""
     _need_cuda(a, b, row_scale, col_scale, out, acc_out)
     M, K = a.shape
     N = b.shape[0] if trans_b else b.shape[1]
     dp = lambda t: None if t is None else t.data_ptr()
     return GemmDesc(dp(a), a.stride(0), dp(b), b.stride(0), 1 if trans_b else 0, M, N, K, dp(row_scale), dp(col_scale),
                     dp(out), _dt(out.dtype) if out is not None else HALO_F32, out.stride(0) if out is not None else 0,
-                    dp(acc_out), acc_out.stride(0) if acc_out is not None else 0)
+                    dp(acc_out), acc_out.stride(0) if acc_out is not None else 0, int(config))
 
 
 def halo_gemm_i8_pair(g1: GemmDesc, g2: GemmDesc) -> None:
@@ -238,9 +242,19 @@ def halo_gemm_i8_pair(g1: GemmDesc, g2: GemmDesc) -> None:
     _check(st, "halo_gemm_i8_pair")
 
 
-def halo_gemm_i8_set_config(config: int) -> None:
-    """Force one GEMM tile configuration (-1 = automatic)."""
-    load_library().halo_gemm_i8_set_config(int(config))
+def halo_gemm_i8_desc(g: GemmDesc) -> None:
+    """One product from a descriptor (tile configuration included)."""
+    st = load_library().halo_gemm_i8_desc(ctypes.byref(g), _stream())
+    _check(st, "halo_gemm_i8_desc")
+
+
+def halo_mfma_i8_probe(operands: torch.Tensor, iters: int, sink: Optional[torch.Tensor] = None) -> float:
+    """Launch the MFMA ceiling probe; returns the number of integer operations it performs."""
+    _need_cuda(operands, sink)
+    assert operands.dtype == torch.int8 and operands.numel() >= 4096 and operands.is_contiguous()
+    st = load_library().halo_mfma_i8_probe(_ptr(operands), int(iters), _ptr(sink), _stream())
+    _check(st, "halo_mfma_i8_probe")
+    return 256.0 * 8 * iters * 16 * 65536.0
 
 
 def halo_dequant_unrotate(acc: torch.Tensor, row_scale: Optional[torch.Tensor], *, had_block: int = 0,

@@ -10,15 +10,15 @@
 // (BM/WAVES_M) x (BN/WAVES_N) sub-tile as a grid of 32x32 MFMA tiles.
 //
 // Main loops:
-//   * "dma", all operands (the fast path): an NS-deep ring of LDS stages filled by global_load_lds_dwordx4 (global
-//     memory -> LDS without passing through registers).  Exactly one K step is issued per iteration, sliced between
-//     the MFMA sub-steps, so the s_waitcnt vmcnt(n) that waits for the oldest stage only is a constant; one s_barrier
-//     per K step.  A K-contiguous operand is stored [row][BK bytes]; a K-strided B is stored as it lies in memory
-//     (K-major rows of BN bytes) and transposed by the LDS read itself, ds_read_b64_tr_b8: a group of 16 lanes reads an
-//     8(k) x 16(n) byte block, lane i supplying the address of row i/2, half i%2, and receiving column i.
-//   * "dma" for A with a register-transposed B (4x4 byte blocks through v_perm_b32): K-strided B whose K is not a
-//     multiple of the K step (the DMA cannot zero-fill a K tail).
-//   * "staged": two LDS stages, next K step prefetched in registers; K-contiguous B with a ragged K.
+//   * "dma" (every K that is a multiple of the K step): an NS-deep ring of LDS stages filled by
+//     global_load_lds_dwordx4 (global memory -> LDS without passing through registers).  Exactly one K step is issued
+//     per iteration, sliced between the MFMA sub-steps, so the s_waitcnt vmcnt(n) that waits for the oldest stage only
+//     is a constant; one s_barrier per K step.  A K-contiguous operand is stored [row][BK bytes]; a K-strided B is
+//     stored as it lies in memory (K-major rows of BN bytes) and transposed by the LDS read itself,
+//     ds_read_b64_tr_b8: a group of 16 lanes reads an 8(k) x 16(n) byte block, lane i supplying the address of row
+//     i/2, half i%2, and receiving column i.
+//   * "staged" (ragged K): two LDS stages of a 128 x 128 tile, the next K step prefetched in registers and zero-filled
+//     beyond K; a K-strided B is transposed in registers (4x4 byte blocks through v_perm_b32).
 // A launch may carry two independent products (halo_gemm_i8_pair): workgroups past the first product's tile count
 // take the second argument block.
 //
@@ -32,7 +32,17 @@
 // by one quarter-wave ds_read_b128 fall in 16 different bank groups (measured: zero LDS bank conflicts); a DMA lane
 // writes LDS slot (wave slot base + lane), so the swizzle is applied to the global address it fetches.  K-major B:
 // chunks XOR-swizzled by 2*(row % 8) (BN = 256) so that the two lane groups of one transposing read stay on even and
-// odd chunks.  Register-transposed B: dwords of four consecutive k, laid out [k/4][n] with a row pitch of BN+8 dwords.
+// odd chunks.  Register-transposed B (staged loop): dwords of four consecutive k, laid out [k/4][n] with a row pitch
+// of BN+8 dwords.
+//
+// What bounds it.  A loop of nothing but these MFMAs sustains 4.9 POP/s on constant operands but only about 3.5 POP/s
+// on random int8 operands (the chip lowers its clock as the multiplier arrays toggle), and about 2.9 POP/s once the
+// LDS fragment reads and the global->LDS stream of a 256 x 256 tile run beside them: the published 5.0 POP/s is not
+// reachable on real data (halo_mfma_i8_probe measures these ceilings on the machine at hand).  That is also why
+// deeper rings, longer K steps, four instead of eight wavefronts, accumulators in AGPRs or a strict
+// memory-phase/MFMA-phase alternation of the two wavefronts of a SIMD all land on the same throughput.
+#include <mutex>
+
 #include "halo_internal.h"
 
 namespace halo {
@@ -41,10 +51,6 @@ namespace {
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 typedef int v2i __attribute__((ext_vector_type(2)));
-
-#ifndef HALO_GEMM_SPREAD_DMA
-#define HALO_GEMM_SPREAD_DMA 1
-#endif
 
 #define HALO_GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void*)(p))
 #define HALO_LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
@@ -55,7 +61,7 @@ __device__ __forceinline__ uint32_t f32_to_bf16_rne(float f) {
 }
 
 // TR: the K-strided B operand goes to LDS untransposed (K-major rows of BN bytes, by DMA like A) and is transposed
-// by the LDS read itself (ds_read_b64_tr_b8).
+// by the LDS read itself (ds_read_b64_tr_b8).  !TRANSB && !TR: B is transposed in registers (staged loop only).
 template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, bool TRANSB, int NS, bool TR = false>
 struct GemmCfg {
     static constexpr bool IS_TR = TR;
@@ -68,7 +74,7 @@ struct GemmCfg {
     static constexpr int CH = BK / 16;        // 16-byte chunks per K-contiguous row
     static constexpr int RPS = 256 / BK;      // rows per 256-byte sweep of the LDS banks
     static constexpr int KSTEPS = BK / 32;
-    static constexpr int LDB_NN = BN + 8;     // dword pitch of the K-strided layout
+    static constexpr int LDB_NN = BN + 8;     // dword pitch of the register-transposed layout
     static constexpr int A_BYTES = BM * BK;
     static constexpr int CHB = BN / 16;       // 16-byte chunks per K-major row of B (TR)
     static constexpr int RPSB = 256 / BN;     // K-major rows per 256-byte sweep of the LDS banks (TR)
@@ -79,7 +85,7 @@ struct GemmCfg {
     static constexpr int LDS_BYTES = NS * STAGE_BYTES > EPI_BYTES ? NS * STAGE_BYTES : EPI_BYTES;
     static constexpr int SLOTS_A = BM * CH / NT;
     static constexpr int SLOTS_B = BN * CH / NT;                 // transB, and TR (BK rows of BN/16 chunks)
-    static constexpr int BLKS_B = (BK / 4) * (BN / 4) / NT;      // !transB
+    static constexpr int BLKS_B = (BK / 4) * (BN / 4) / NT;      // register-transposed B
     static constexpr int NB = (TRANSB || TR) ? SLOTS_B : BLKS_B;
     static_assert(!TR || (!TRANSB && (BN == 128 || BN == 256)), "TR is for the K-strided B operand");
     static_assert(BM * CH % NT == 0 && BN * CH % NT == 0, "tile/threads mismatch");
@@ -89,7 +95,9 @@ struct GemmCfg {
 
 // Consecutive workgroup ids go to different XCDs (8 per chip): give every XCD a contiguous range of tile
 // numbers, and walk tiles in groups of GROUP tile-rows so that one XCD's resident tiles share A and B panels in
-// its L2 (measured on an 8192^3 product: 22 % L2 misses with this map, 51 % without the XCD step).
+// its L2 (measured on an 8192^3 product: 22 % L2 misses with this map, 51 % without the XCD step).  `bid` counts
+// from the first workgroup of the product: for the second product of a paired launch that rotates the XCD numbers by
+// (first product's workgroups) % 8, which still hands every hardware XCD one contiguous range of tile numbers.
 template <int GROUP>
 __device__ __forceinline__ void tile_of_block(int bid, int tiles_m, int tiles_n, int& tile_m, int& tile_n) {
     const int ntiles = tiles_m * tiles_n;
@@ -119,45 +127,77 @@ __device__ __forceinline__ uint4 transpose4x4(const uint32_t (&r)[4]) {
     return t;
 }
 
-// Operand fragments of K sub-step kk (32 bytes of K) of one LDS stage.
-template <class Cfg, bool TRANSB, int BK>
-__device__ __forceinline__ void load_frags(const unsigned char* sa, const unsigned char* sb, int kk, int wave_m,
-                                           int wave_n, int lrow, int half, v4i (&af)[Cfg::TM], v4i (&bf)[Cfg::TN]) {
+// Operand fragments of one wavefront for one K sub-step (32 bytes of K).  bt holds the halves of the B fragments as
+// the transposing reads deliver them, until wait_frags() has assembled them into b.
+template <class Cfg>
+struct Frags {
+    v4i a[Cfg::TM], b[Cfg::TN];
+    v2i bt[Cfg::TN][2];
+};
+
+// Requests the fragments of K sub-step KK of one LDS stage.
+template <class Cfg, bool TRANSB, int BK, int KK>
+__device__ __forceinline__ void load_frags(const unsigned char* sa, const unsigned char* sb, int wave_m, int wave_n,
+                                           int lrow, int half, Frags<Cfg>& f) {
     constexpr int CH = Cfg::CH, RPS = Cfg::RPS;
-    const int g = 2 * kk + half;
+    const int g = 2 * KK + half;
 #pragma unroll
     for (int i = 0; i < Cfg::TM; ++i) {
         const int row = wave_m * Cfg::WM + i * 32 + lrow;
         const int pc = g ^ ((row / RPS) % CH);
-        af[i] = *reinterpret_cast<const v4i*>(sa + row * BK + 16 * pc);
+        f.a[i] = *reinterpret_cast<const v4i*>(sa + row * BK + 16 * pc);
     }
 #pragma unroll
     for (int j = 0; j < Cfg::TN; ++j) {
         const int col = wave_n * Cfg::WN + j * 32 + lrow;
         if constexpr (TRANSB) {
             const int pc = g ^ ((col / RPS) % CH);
-            bf[j] = *reinterpret_cast<const v4i*>(sb + col * BK + 16 * pc);
+            f.b[j] = *reinterpret_cast<const v4i*>(sb + col * BK + 16 * pc);
         } else if constexpr (Cfg::IS_TR) {
             // A group of 16 lanes reads an 8(k) x 16(n) byte block: lane i supplies the address of 8 bytes of
             // K-major row k0 + i/2 at column offset 8*(i%2) and receives the 8 k-values of column i of the block.
             // Rows are XOR-swizzled by 2*((row / RPSB) % (CHB/2)) chunks, which keeps the two lane groups of one
-            // read on even and odd chunks respectively (no bank conflicts) and is undone by the DMA addresses.
+            // read on even and odd chunks respectively (no bank conflicts) and is undone by the DMA addresses.  The
+            // swizzle term depends on the lane only, so one address per column block serves every K sub-step through
+            // the instruction's immediate offset.
             const int lane16 = (lrow & 15), gsel = lrow >> 4;
             const int chunk = (wave_n * Cfg::WN + j * 32) / 16 + gsel;
-#pragma unroll
-            for (int q = 0; q < 2; ++q) {
-                const int krow = 32 * kk + 16 * half + 8 * q + (lane16 >> 1);
-                const int pc = chunk ^ (2 * ((krow / Cfg::RPSB) % (Cfg::CHB / 2)));
-                const v2i r = __builtin_amdgcn_ds_read_tr8_b64_v2i32(
-                    (__attribute__((address_space(3))) v2i*)(sb + krow * Cfg::BN_ + 16 * pc + 8 * (lane16 & 1)));
-                bf[j][2 * q] = r[0];
-                bf[j][2 * q + 1] = r[1];
-            }
+            const int s8 = lane16 >> 1;
+            const int pc = chunk ^ (2 * ((s8 / Cfg::RPSB) % (Cfg::CHB / 2)));
+            const uint32_t addr =
+                (uint32_t)(uintptr_t)HALO_LDS_PTR(sb + (16 * half + s8) * Cfg::BN_ + 16 * pc + 8 * (lane16 & 1));
+            // Issued as inline assembly: seen as an LDS read, the compiler would order it after every outstanding
+            // global->LDS transfer (s_waitcnt vmcnt(0)), which empties the ring at every K step.  wait_frags() waits
+            // for the data before the MFMAs that use it.
+            asm volatile("ds_read_b64_tr_b8 %0, %2 offset:%3\n\tds_read_b64_tr_b8 %1, %2 offset:%4"
+                         : "=&v"(f.bt[j][0]), "=&v"(f.bt[j][1])
+                         : "v"(addr), "n"(32 * KK * Cfg::BN_), "n"((32 * KK + 8) * Cfg::BN_));
         } else {
             const uint32_t* sbw = reinterpret_cast<const uint32_t*>(sb);
 #pragma unroll
-            for (int w = 0; w < 4; ++w) bf[j][w] = (int)sbw[(4 * g + w) * Cfg::LDB_NN + col];
+            for (int w = 0; w < 4; ++w) f.b[j][w] = (int)sbw[(4 * g + w) * Cfg::LDB_NN + col];
         }
+    }
+}
+
+// Waits for the transposing LDS reads issued by load_frags (the compiler does not track them) and assembles the B
+// fragments.  The registers are operands of the wait, so nothing that uses them can move above it.
+template <class Cfg>
+__device__ __forceinline__ void wait_frags(Frags<Cfg>& f) {
+    auto& bt = f.bt;
+    if constexpr (Cfg::TN == 1) {
+        asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(bt[0][0]), "+v"(bt[0][1]));
+    } else if constexpr (Cfg::TN == 2) {
+        asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(bt[0][0]), "+v"(bt[0][1]), "+v"(bt[1][0]), "+v"(bt[1][1]));
+    } else {
+        static_assert(Cfg::TN == 4, "B fragments per wavefront");
+        asm volatile("s_waitcnt lgkmcnt(0)"
+                     : "+v"(bt[0][0]), "+v"(bt[0][1]), "+v"(bt[1][0]), "+v"(bt[1][1]), "+v"(bt[2][0]), "+v"(bt[2][1]),
+                       "+v"(bt[3][0]), "+v"(bt[3][1]));
+    }
+#pragma unroll
+    for (int j = 0; j < Cfg::TN; ++j) {
+        f.b[j][0] = bt[j][0][0]; f.b[j][1] = bt[j][0][1]; f.b[j][2] = bt[j][1][0]; f.b[j][3] = bt[j][1][1];
     }
 }
 
@@ -189,29 +229,40 @@ struct NoBetween {
     __device__ __forceinline__ void operator()(int) const {}
 };
 
-// All MFMAs of one LDS stage; the fragments of sub-step kk+1 are requested while the MFMAs of sub-step kk run.
-// between(kk) is called after the MFMAs of sub-step kk (all but the last): the DMA kernels issue a slice of the
-// next K step's global->LDS loads there; VM = number of such instructions per call (for the scheduling recipe).
+// Sub-step KK of one LDS stage: the fragments of sub-step KK+1 are requested while the MFMAs of sub-step KK run.
+template <class Cfg, bool TRANSB, int BK, int KK, class Between>
+__device__ __forceinline__ void mma_substep(const unsigned char* sa, const unsigned char* sb, int wave_m, int wave_n,
+                                            int lrow, int half, v16i (&acc)[Cfg::TM][Cfg::TN], const Between& between,
+                                            Frags<Cfg>& cur) {
+    constexpr int TM = Cfg::TM, TN = Cfg::TN;
+    if constexpr (Cfg::IS_TR) wait_frags<Cfg>(cur);
+    Frags<Cfg> nxt;
+    if constexpr (KK + 1 < Cfg::KSTEPS) load_frags<Cfg, TRANSB, BK, KK + 1>(sa, sb, wave_m, wave_n, lrow, half, nxt);
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(cur.a[i], cur.b[j], acc[i][j], 0, 0, 0);
+    if constexpr (KK + 1 < Cfg::KSTEPS) {
+        between(KK);
+        mma_substep<Cfg, TRANSB, BK, KK + 1, Between>(sa, sb, wave_m, wave_n, lrow, half, acc, between, nxt);
+    }
+}
+
+// All MFMAs of one LDS stage.  between(kk) is called after the MFMAs of sub-step kk (all but the last): the DMA kernel
+// issues a slice of the next K step's global->LDS loads there; VM = number of such instructions per call (for the
+// scheduling recipe).
 template <class Cfg, bool TRANSB, int BK, int VM = 0, class Between = NoBetween>
 __device__ __forceinline__ void mma_stage(const unsigned char* sa, const unsigned char* sb, int wave_m, int wave_n,
                                           int lrow, int half, v16i (&acc)[Cfg::TM][Cfg::TN],
                                           const Between& between = Between()) {
     constexpr int TM = Cfg::TM, TN = Cfg::TN;
-    constexpr int READS = TM + (TRANSB ? TN : (Cfg::IS_TR ? 2 * TN : 4 * TN));     // LDS read instructions per sub-step
+    // LDS read instructions per sub-step that the scheduler sees (the transposing reads are inline assembly)
+    constexpr int READS = TM + (TRANSB ? TN : (Cfg::IS_TR ? 0 : 4 * TN));
     constexpr int MFMAS = TM * TN;
-    v4i af[2][TM], bf[2][TN];
-    load_frags<Cfg, TRANSB, BK>(sa, sb, 0, wave_m, wave_n, lrow, half, af[0], bf[0]);
-#pragma unroll
-    for (int kk = 0; kk < Cfg::KSTEPS; ++kk) {
-        if (kk + 1 < Cfg::KSTEPS)
-            load_frags<Cfg, TRANSB, BK>(sa, sb, kk + 1, wave_m, wave_n, lrow, half, af[(kk + 1) & 1], bf[(kk + 1) & 1]);
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int j = 0; j < TN; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[kk & 1][i], bf[kk & 1][j], acc[i][j], 0, 0, 0);
-        if (kk + 1 < Cfg::KSTEPS) between(kk);
-    }
+    Frags<Cfg> first;
+    load_frags<Cfg, TRANSB, BK, 0>(sa, sb, wave_m, wave_n, lrow, half, first);
+    mma_substep<Cfg, TRANSB, BK, 0, Between>(sa, sb, wave_m, wave_n, lrow, half, acc, between, first);
     __builtin_amdgcn_sched_group_barrier(0x100, READS, 0);
     StageSched<0, (Cfg::KSTEPS - 1) * MFMAS, MFMAS, READS, VM>::run();
 }
@@ -220,7 +271,9 @@ __device__ __forceinline__ void mma_stage(const unsigned char* sa, const unsigne
 // scattered over 32 rows, so each wavefront first drops a 32-row slab of its sub-tile into a private LDS region
 // (one dword per element, row pitch WN+8 dwords: conflict-free writes) and reads it back four consecutive
 // columns per lane, which turns the global stores into 16-byte (int32/fp32) or 8-byte (bf16) pieces of fully
-// covered rows.  Only the owning wavefront touches its region, so no barrier is needed after the first one.
+// covered rows.  Only the owning wavefront touches its region, so after the first barrier the wavefront only has to
+// order its own LDS writes and reads (the lanes of a wavefront run in lockstep; the wavefront-scope fences keep the
+// compiler from moving the accesses across the slab boundaries).
 template <class Cfg>
 __device__ __forceinline__ void epilogue(const GemmArgs& a, int64_t m0, int64_t n0, int wave, int wave_m, int wave_n,
                                          int lane, const v16i (&acc)[Cfg::TM][Cfg::TN], unsigned char* smem) {
@@ -242,11 +295,15 @@ __device__ __forceinline__ void epilogue(const GemmArgs& a, int64_t m0, int64_t 
     }
 #pragma unroll
     for (int i = 0; i < Cfg::TM; ++i) {
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");   // the read-back of the previous slab is complete
+        __builtin_amdgcn_wave_barrier();
 #pragma unroll
         for (int j = 0; j < Cfg::TN; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r)
                 region[(8 * (r / 4) + 4 * half + (r % 4)) * PITCH + j * 32 + lrow] = (uint32_t)acc[i][j][r];
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");   // the slab is written before other lanes read it
+        __builtin_amdgcn_wave_barrier();
 #pragma unroll
         for (int p = 0; p < 32 / RPP; ++p) {
             const int rr = p * RPP + lane / LPR;
@@ -294,25 +351,12 @@ __device__ __forceinline__ void epilogue(const GemmArgs& a, int64_t m0, int64_t 
     }
 }
 
-// s_waitcnt vmcnt(n) lgkmcnt(0) with n chosen at run time (the instruction takes an immediate).
-#define HALO_WAIT_CASE(N) case N: asm volatile("s_waitcnt vmcnt(" #N ") lgkmcnt(0)" ::: "memory"); break;
-__device__ __forceinline__ void wait_vmcnt_lgkm0(int n) {
-    switch (n) {
-        HALO_WAIT_CASE(1) HALO_WAIT_CASE(2) HALO_WAIT_CASE(3) HALO_WAIT_CASE(4) HALO_WAIT_CASE(5) HALO_WAIT_CASE(6)
-        HALO_WAIT_CASE(7) HALO_WAIT_CASE(8) HALO_WAIT_CASE(9) HALO_WAIT_CASE(10) HALO_WAIT_CASE(11) HALO_WAIT_CASE(12)
-        HALO_WAIT_CASE(13) HALO_WAIT_CASE(14) HALO_WAIT_CASE(15) HALO_WAIT_CASE(16) HALO_WAIT_CASE(17) HALO_WAIT_CASE(18)
-        HALO_WAIT_CASE(19) HALO_WAIT_CASE(20) HALO_WAIT_CASE(21) HALO_WAIT_CASE(22) HALO_WAIT_CASE(23) HALO_WAIT_CASE(24)
-        HALO_WAIT_CASE(25) HALO_WAIT_CASE(26) HALO_WAIT_CASE(27) HALO_WAIT_CASE(28) HALO_WAIT_CASE(29) HALO_WAIT_CASE(30)
-        HALO_WAIT_CASE(31) HALO_WAIT_CASE(32)
-        default: asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory"); break;   // 0, or anything out of range
-    }
-}
-
 // ------------------------------------------------------------------------------------------------ dma main loop
-template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, bool TRANSB, int NS, bool TR = false>
+// Both operands go through the DMA ring.  K must be a multiple of BK (the DMA cannot zero-fill a K tail).
+template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, bool TRANSB, int NS>
 __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N)
 gemm_i8_dma_kernel(GemmArgs a, int tiles_m, int tiles_n, GemmArgs a2, int tiles_m2, int tiles_n2, unsigned blocks1) {
-    using Cfg = GemmCfg<BM, BN, BK, WAVES_M, WAVES_N, TRANSB, NS, TR>;
+    using Cfg = GemmCfg<BM, BN, BK, WAVES_M, WAVES_N, TRANSB, NS, !TRANSB>;
     // A second, independent product may ride in the same launch (workgroups from blocks1 on): the tail and the
     // epilogue of one then overlap the main loop of the other.
     int bid = blockIdx.x;
@@ -322,11 +366,9 @@ gemm_i8_dma_kernel(GemmArgs a, int tiles_m, int tiles_n, GemmArgs a2, int tiles_
         tiles_m = tiles_m2;
         tiles_n = tiles_n2;
     }
-    constexpr bool BOTH_DMA = TRANSB || TR;   // both operands go through the DMA ring
     constexpr int NT = Cfg::NT, CH = Cfg::CH, RPS = Cfg::RPS, TM = Cfg::TM, TN = Cfg::TN;
     constexpr int D = NS - 1;                                     // K steps in flight
-    constexpr int LOADS = Cfg::SLOTS_A + Cfg::SLOTS_B;      // DMA loads per K step when both operands use the ring
-    static_assert((NS - 2) * LOADS <= 32 && (NS - 2) * Cfg::SLOTS_A + 4 * Cfg::BLKS_B <= 32, "wait table too small");
+    constexpr int LOADS = Cfg::SLOTS_A + Cfg::SLOTS_B;            // DMA loads per thread per K step
     extern __shared__ __align__(16) unsigned char smem[];
 
     const int tid = threadIdx.x;
@@ -340,11 +382,11 @@ gemm_i8_dma_kernel(GemmArgs a, int tiles_m, int tiles_n, GemmArgs a2, int tiles_
     tile_of_block<Cfg::GROUP_M>(bid, tiles_m, tiles_n, tile_m, tile_n);
     const int64_t m0 = (int64_t)tile_m * BM;
     const int64_t n0 = (int64_t)tile_n * BN;
-    const int nk = (int)((a.K + BK - 1) / BK);
+    const int nk = (int)(a.K / BK);
 
-    // ---- per-thread source addresses (fixed over the K loop)
+    // ---- per-thread source addresses (fixed over the K loop); rows beyond the matrix are clamped, their results
+    // are never stored
     const int8_t* a_src[Cfg::SLOTS_A];
-    int a_koff[Cfg::SLOTS_A];
 #pragma unroll
     for (int i = 0; i < Cfg::SLOTS_A; ++i) {
         const int p = tid + i * NT;
@@ -352,111 +394,46 @@ gemm_i8_dma_kernel(GemmArgs a, int tiles_m, int tiles_n, GemmArgs a2, int tiles_
         const int g = pc ^ ((row / RPS) % CH);
         int64_t gr = m0 + row;
         if (gr > a.M - 1) gr = a.M - 1;
-        a_src[i] = a.A + gr * a.lda;
-        a_koff[i] = 16 * g;
+        a_src[i] = a.A + gr * a.lda + 16 * g;
     }
-    const int8_t* b_src[Cfg::NB];
-    int b_koff[Cfg::NB];
-    bool b_ok[Cfg::NB];
-    if constexpr (TRANSB) {
+    const int8_t* b_src[Cfg::SLOTS_B];
 #pragma unroll
-        for (int i = 0; i < Cfg::SLOTS_B; ++i) {
-            const int p = tid + i * NT;
+    for (int i = 0; i < Cfg::SLOTS_B; ++i) {
+        const int p = tid + i * NT;
+        if constexpr (TRANSB) {
             const int row = p / CH, pc = p % CH;
             const int g = pc ^ ((row / RPS) % CH);
             int64_t gr = n0 + row;
             if (gr > a.N - 1) gr = a.N - 1;
-            b_src[i] = a.B + gr * a.ldb;
-            b_koff[i] = 16 * g;
-            b_ok[i] = true;
-        }
-    } else if constexpr (TR) {
-        // K-major rows of BN bytes; LDS slot (row, pc) holds chunk pc ^ swizzle(row) of that row.  A chunk whose
-        // columns start beyond the row pitch is replaced by chunk 0 (those columns are never stored).
-#pragma unroll
-        for (int i = 0; i < Cfg::SLOTS_B; ++i) {
-            const int p = tid + i * NT;
+            b_src[i] = a.B + gr * a.ldb + 16 * g;
+        } else {
+            // K-major rows of BN bytes; LDS slot (row, pc) holds chunk pc ^ swizzle(row) of that row.  A chunk whose
+            // columns start beyond the row pitch is replaced by chunk 0 (those columns are never stored).
             const int row = p / Cfg::CHB, pc = p % Cfg::CHB;
             const int c = pc ^ (2 * ((row / Cfg::RPSB) % (Cfg::CHB / 2)));
             int64_t colb = n0 + 16 * c;
             if (colb >= a.ldb) colb = 0;
             b_src[i] = a.B + (int64_t)row * a.ldb + colb;
-            b_koff[i] = row;
-            b_ok[i] = true;
-        }
-    } else {
-#pragma unroll
-        for (int i = 0; i < Cfg::BLKS_B; ++i) {
-            const int q = tid + i * NT;
-            const int nb = q % (BN / 4), kb = q / (BN / 4);
-            b_ok[i] = (n0 + 4 * nb) < a.N;
-            b_src[i] = a.B + (b_ok[i] ? n0 + 4 * nb : 0);
-            b_koff[i] = 4 * kb;
         }
     }
+    const int64_t b_step = TRANSB ? (int64_t)BK : (int64_t)BK * a.ldb;
 
-    // DMA of the K-contiguous operand(s) of K step t into ring slot t % NS.  A chunk that lies beyond K (only
-    // possible for A of the K-strided case, where the matching B rows are zero) is fetched from offset 0 instead.
-    // lo..hi select a sub-range of the step's DMA instructions (A slots first, then B slots), so that the caller
-    // can thread them between the MFMAs instead of issuing one burst.
-    auto issue_dma = [&](int t, int src_step = -1, int lo = 0, int hi = 1 << 20) {
+    // DMA of K step src into ring slot t % NS.  lo..hi select a sub-range of the step's DMA instructions (A slots
+    // first, then B slots), so that the caller can thread them between the MFMAs instead of issuing one burst.
+    auto issue_dma = [&](int t, int src, int lo = 0, int hi = 1 << 20) {
         unsigned char* sa = smem + (t % NS) * Cfg::STAGE_BYTES;
-        const int64_t k0 = (int64_t)(src_step < 0 ? t : src_step) * BK;
+        unsigned char* sb = sa + Cfg::A_BYTES;
 #pragma unroll
         for (int i = 0; i < Cfg::SLOTS_A; ++i) {
             if (i < lo || i >= hi) continue;
-            int64_t k = k0 + a_koff[i];
-            if (k >= a.K) k = 0;
-            __builtin_amdgcn_global_load_lds(HALO_GLOBAL_PTR(a_src[i] + k),
+            __builtin_amdgcn_global_load_lds(HALO_GLOBAL_PTR(a_src[i] + (int64_t)src * BK),
                                              HALO_LDS_PTR(sa + (wave * 64 + i * NT) * 16), 16, 0, 0);
         }
-        if constexpr (TRANSB) {
-            unsigned char* sb = sa + Cfg::A_BYTES;
 #pragma unroll
-            for (int i = 0; i < Cfg::SLOTS_B; ++i) {
-                if (Cfg::SLOTS_A + i < lo || Cfg::SLOTS_A + i >= hi) continue;
-                __builtin_amdgcn_global_load_lds(HALO_GLOBAL_PTR(b_src[i] + k0 + b_koff[i]),
-                                                 HALO_LDS_PTR(sb + (wave * 64 + i * NT) * 16), 16, 0, 0);
-            }
-        } else if constexpr (TR) {
-            unsigned char* sb = sa + Cfg::A_BYTES;
-#pragma unroll
-            for (int i = 0; i < Cfg::SLOTS_B; ++i) {
-                if (Cfg::SLOTS_A + i < lo || Cfg::SLOTS_A + i >= hi) continue;
-                __builtin_amdgcn_global_load_lds(HALO_GLOBAL_PTR(b_src[i] + k0 * a.ldb),
-                                                 HALO_LDS_PTR(sb + (wave * 64 + i * NT) * 16), 16, 0, 0);
-            }
-        }
-    };
-
-    // K-strided B: unconditional (address-clamped) dword loads so that the number of loads per K step is fixed;
-    // rows beyond K and columns beyond N are zeroed after the load.
-    uint32_t b_raw[BOTH_DMA ? 1 : Cfg::BLKS_B][4];
-    auto load_b_regs = [&](int t) {
-        if constexpr (!BOTH_DMA) {
-            const int64_t k0 = (int64_t)t * BK;
-#pragma unroll
-            for (int i = 0; i < Cfg::BLKS_B; ++i) {
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    int64_t k = k0 + b_koff[i] + j;
-                    const bool ok = b_ok[i] && k < a.K;
-                    if (k > a.K - 1) k = a.K - 1;
-                    const uint32_t v = *reinterpret_cast<const uint32_t*>(b_src[i] + k * a.ldb);
-                    b_raw[i][j] = ok ? v : 0u;
-                }
-            }
-        }
-    };
-    auto store_b_lds = [&](int t) {
-        if constexpr (!BOTH_DMA) {
-            unsigned char* sb = smem + (t % NS) * Cfg::STAGE_BYTES + Cfg::A_BYTES;
-#pragma unroll
-            for (int i = 0; i < Cfg::BLKS_B; ++i) {
-                const int q = tid + i * NT;
-                const int nb = q % (BN / 4), kb = q / (BN / 4);
-                *reinterpret_cast<uint4*>(sb + (kb * Cfg::LDB_NN + 4 * nb) * 4) = transpose4x4(b_raw[i]);
-            }
+        for (int i = 0; i < Cfg::SLOTS_B; ++i) {
+            if (Cfg::SLOTS_A + i < lo || Cfg::SLOTS_A + i >= hi) continue;
+            __builtin_amdgcn_global_load_lds(HALO_GLOBAL_PTR(b_src[i] + (int64_t)src * b_step),
+                                             HALO_LDS_PTR(sb + (wave * 64 + i * NT) * 16), 16, 0, 0);
         }
     };
 
@@ -469,48 +446,23 @@ gemm_i8_dma_kernel(GemmArgs a, int tiles_m, int tiles_n, GemmArgs a2, int tiles_
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
 
     if (nk > 0) {
-        if constexpr (BOTH_DMA) {
-            // Every iteration issues exactly one K step (beyond the end: the last step again, into a ring slot
-            // nobody reads), so the loop body is one straight block with a constant wait count.
-            for (int t = 0; t < D; ++t) issue_dma(t, t < nk ? t : nk - 1);
-            for (int kt = 0; kt < nk; ++kt) {
-                asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"((D - 1) * LOADS) : "memory");
-                __builtin_amdgcn_s_barrier();
-                asm volatile("" ::: "memory");
-                // ring slot (kt-1) % NS: everyone is past reading it
-                const int src = kt + D < nk ? kt + D : nk - 1;
-                const unsigned char* sa = smem + (kt % NS) * Cfg::STAGE_BYTES;
-                if constexpr (HALO_GEMM_SPREAD_DMA && Cfg::KSTEPS > 1 && LOADS % (Cfg::KSTEPS - 1) == 0) {
-                    constexpr int PER = LOADS / (Cfg::KSTEPS - 1);
-                    auto between = [&](int kk) { issue_dma(kt + D, src, kk * PER, (kk + 1) * PER); };
-                    mma_stage<Cfg, TRANSB, BK, PER>(sa, sa + Cfg::A_BYTES, wave_m, wave_n, lrow, half, acc, between);
-                } else {
-                    issue_dma(kt + D, src);
-                    mma_stage<Cfg, TRANSB, BK>(sa, sa + Cfg::A_BYTES, wave_m, wave_n, lrow, half, acc);
-                }
-            }
-        } else {
-            // A: DMA ring, D K steps in flight.  B: registers, loaded one K step ahead of the LDS write that
-            // happens one K step ahead of its use.
-            load_b_regs(0);
-            store_b_lds(0);
-            if (nk > 1) load_b_regs(1);
-            for (int t = 0; t < D && t < nk; ++t) issue_dma(t);
-            for (int kt = 0; kt < nk; ++kt) {
-                // Loads issued after the DMA of A step kt: the DMAs of A steps kt+1..min(kt+D-1,nk-1) and, from
-                // the second iteration on, the register loads of B step kt+1 (issued at the end of step kt-1).
-                int later = nk - 1 - kt;
-                if (later > D - 1) later = D - 1;
-                wait_vmcnt_lgkm0(later * Cfg::SLOTS_A + ((kt >= 1 && kt + 1 < nk) ? 4 * Cfg::BLKS_B : 0));
-                __builtin_amdgcn_s_barrier();
-                asm volatile("" ::: "memory");
-                if (kt + D < nk) issue_dma(kt + D);
-                const unsigned char* sa = smem + (kt % NS) * Cfg::STAGE_BYTES;
+        // Every iteration issues exactly one K step (beyond the end: the last step again, into a ring slot nobody
+        // reads), so the loop body is one straight block with a constant wait count.
+        for (int t = 0; t < D; ++t) issue_dma(t, t < nk ? t : nk - 1);
+        for (int kt = 0; kt < nk; ++kt) {
+            asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"((D - 1) * LOADS) : "memory");
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+            // ring slot (kt-1) % NS: everyone is past reading it
+            const int src = kt + D < nk ? kt + D : nk - 1;
+            const unsigned char* sa = smem + (kt % NS) * Cfg::STAGE_BYTES;
+            if constexpr (Cfg::KSTEPS > 1 && LOADS % (Cfg::KSTEPS - 1) == 0) {
+                constexpr int PER = LOADS / (Cfg::KSTEPS - 1);
+                auto between = [&](int kk) { issue_dma(kt + D, src, kk * PER, (kk + 1) * PER); };
+                mma_stage<Cfg, TRANSB, BK, PER>(sa, sa + Cfg::A_BYTES, wave_m, wave_n, lrow, half, acc, between);
+            } else {
+                issue_dma(kt + D, src);
                 mma_stage<Cfg, TRANSB, BK>(sa, sa + Cfg::A_BYTES, wave_m, wave_n, lrow, half, acc);
-                if (kt + 1 < nk) {
-                    store_b_lds(kt + 1);                   // ring slot (kt+1) % NS was last read at step kt+1-NS
-                    if (kt + 2 < nk) load_b_regs(kt + 2);
-                }
             }
         }
         asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
@@ -651,140 +603,137 @@ gemm_i8_staged_kernel(GemmArgs a, int tiles_m, int tiles_n) {
     epilogue<Cfg>(a, m0, n0, wave, wave_m, wave_n, lane, acc, smem);
 }
 
-// ------------------------------------------------------------------------------------------------ launch
-int g_forced_config = -1;
-int g_pair_backward = 1;         // 0: never put the two backward products into one launch (measurement aid)
-int g_nn_transpose_in_lds = 1;   // 0: transpose the K-strided operand in registers instead (measurement aid)
-
-template <class Kern>
-hipError_t launch_kernel(Kern kern, int lds_bytes, int threads, int bm, int bn, const GemmArgs& a, hipStream_t s,
-                         bool* attr_set) {
-    if (!*attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
-        if (e != hipSuccess) return e;
-        *attr_set = true;
+// ------------------------------------------------------------------------------------------------ ceiling probe
+// iters x 16 MFMAs per wavefront on operands read once from `operands` (4 KB: 16 bytes per lane and fragment, four
+// fragments), nothing else in the loop: the rate the matrix pipes sustain on this machine for this operand data.
+__global__ void __launch_bounds__(512) mfma_i8_probe_kernel(const int8_t* operands, int iters, int32_t* sink) {
+    const int lane = threadIdx.x & 63;
+    v4i f[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) f[i] = *reinterpret_cast<const v4i*>(operands + (i * 64 + lane) * 16);
+    v16i acc[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][r] = 0;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int m = 0; m < 16; ++m)
+            acc[m % 8] = __builtin_amdgcn_mfma_i32_32x32x32_i8(f[m % 2], f[2 + (m / 2) % 2], acc[m % 8], 0, 0, 0);
     }
-    const int tiles_m = (int)((a.M + bm - 1) / bm), tiles_n = (int)((a.N + bn - 1) / bn);
-    hipLaunchKernelGGL(kern, dim3((unsigned)(tiles_m * tiles_n)), dim3(threads), lds_bytes, s, a, tiles_m, tiles_n);
-    return hipGetLastError();
+    int s = 0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s += acc[i][r];
+    if (sink && s == 0x7fffffff) sink[0] = s;      // keeps the loop alive; practically never taken
 }
 
+// ------------------------------------------------------------------------------------------------ launch
+// The dynamic-LDS limit of a kernel is raised once per kernel (and per process); call_once makes that safe when
+// several host threads launch the same kernel for the first time.
 template <class Kern>
-hipError_t launch_kernel_pair(Kern kern, int lds_bytes, int threads, int bm, int bn, const GemmArgs& a, const GemmArgs* a2,
-                              hipStream_t s, bool* attr_set) {
-    if (!*attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
-        if (e != hipSuccess) return e;
-        *attr_set = true;
-    }
-    const int tiles_m = (int)((a.M + bm - 1) / bm), tiles_n = (int)((a.N + bn - 1) / bn);
-    const unsigned blocks1 = (unsigned)(tiles_m * tiles_n);
-    int tiles_m2 = 0, tiles_n2 = 0;
-    if (a2) {
-        tiles_m2 = (int)((a2->M + bm - 1) / bm);
-        tiles_n2 = (int)((a2->N + bn - 1) / bn);
-    }
-    hipLaunchKernelGGL(kern, dim3(blocks1 + (unsigned)(tiles_m2 * tiles_n2)), dim3(threads), lds_bytes, s, a, tiles_m,
-                       tiles_n, a2 ? *a2 : a, tiles_m2, tiles_n2, blocks1);
-    return hipGetLastError();
+hipError_t raise_lds_limit(Kern kern, int lds_bytes, std::once_flag* once, hipError_t* result) {
+    std::call_once(*once, [&] {
+        *result = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                      lds_bytes);
+    });
+    return *result;
 }
 
 template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, bool TRANSB, int NS>
 hipError_t launch_dma(const GemmArgs& a, hipStream_t s, const GemmArgs* a2 = nullptr) {
-    if constexpr (!TRANSB) {
-        // K-strided B: the LDS-transposing path needs whole K steps (it cannot zero-fill a K tail)
-        if (a.K % BK == 0 && g_nn_transpose_in_lds) {
-            using Cfg = GemmCfg<BM, BN, BK, WAVES_M, WAVES_N, false, NS, true>;
-            static bool attr_set_tr = false;
-            return launch_kernel_pair(gemm_i8_dma_kernel<BM, BN, BK, WAVES_M, WAVES_N, false, NS, true>, Cfg::LDS_BYTES, Cfg::NT,
-                                 BM, BN, a, a2, s, &attr_set_tr);
-        }
+    using Cfg = GemmCfg<BM, BN, BK, WAVES_M, WAVES_N, TRANSB, NS, !TRANSB>;
+    static std::once_flag once;
+    static hipError_t attr_result = hipSuccess;
+    auto kern = gemm_i8_dma_kernel<BM, BN, BK, WAVES_M, WAVES_N, TRANSB, NS>;
+    hipError_t e = raise_lds_limit(kern, Cfg::LDS_BYTES, &once, &attr_result);
+    if (e != hipSuccess) return e;
+    if (a.K % BK != 0 || (a2 && a2->K % BK != 0)) return hipErrorInvalidValue;
+    const int tiles_m = (int)((a.M + BM - 1) / BM), tiles_n = (int)((a.N + BN - 1) / BN);
+    const unsigned blocks1 = (unsigned)(tiles_m * tiles_n);
+    int tiles_m2 = 0, tiles_n2 = 0;
+    if (a2) {
+        tiles_m2 = (int)((a2->M + BM - 1) / BM);
+        tiles_n2 = (int)((a2->N + BN - 1) / BN);
     }
-    using Cfg = GemmCfg<BM, BN, BK, WAVES_M, WAVES_N, TRANSB, NS>;
-    static bool attr_set = false;
-    return launch_kernel_pair(gemm_i8_dma_kernel<BM, BN, BK, WAVES_M, WAVES_N, TRANSB, NS>, Cfg::LDS_BYTES, Cfg::NT, BM, BN,
-                         a, a2, s, &attr_set);
+    hipLaunchKernelGGL(kern, dim3(blocks1 + (unsigned)(tiles_m2 * tiles_n2)), dim3(Cfg::NT), Cfg::LDS_BYTES, s, a, tiles_m,
+                       tiles_n, a2 ? *a2 : a, tiles_m2, tiles_n2, blocks1);
+    return hipGetLastError();
 }
 
-template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, bool TRANSB>
+template <bool TRANSB>
 hipError_t launch_staged(const GemmArgs& a, hipStream_t s) {
-    using Cfg = GemmCfg<BM, BN, BK, WAVES_M, WAVES_N, TRANSB, 2>;
-    static bool attr_set = false;
-    return launch_kernel(gemm_i8_staged_kernel<BM, BN, BK, WAVES_M, WAVES_N, TRANSB>, Cfg::LDS_BYTES, Cfg::NT, BM, BN, a,
-                         s, &attr_set);
+    using Cfg = GemmCfg<128, 128, 64, 2, 2, TRANSB, 2>;
+    static std::once_flag once;
+    static hipError_t attr_result = hipSuccess;
+    auto kern = gemm_i8_staged_kernel<128, 128, 64, 2, 2, TRANSB>;
+    hipError_t e = raise_lds_limit(kern, Cfg::LDS_BYTES, &once, &attr_result);
+    if (e != hipSuccess) return e;
+    const int tiles_m = (int)((a.M + 127) / 128), tiles_n = (int)((a.N + 127) / 128);
+    hipLaunchKernelGGL(kern, dim3((unsigned)(tiles_m * tiles_n)), dim3(Cfg::NT), Cfg::LDS_BYTES, s, a, tiles_m, tiles_n);
+    return hipGetLastError();
 }
 
-// Configurations (macro tile M x N x K-step bytes, wavefronts, ring depth):
-//   0: 256x256x64  8w NS4     1: 256x128x64 8w NS4     2: 128x128x64 4w NS4     3: 128x256x64 8w NS4
-//   4: 256x256x128 8w NS2     5: 256x128x128 8w(2x4) NS3   6: 256x128x128 4w(2x2) NS3
-//   7: 128x256x128 8w(2x4) NS3   8: 256x128x128 8w(4x2) NS3   9: 128x128x64 4w NS3   10: 128x256x64 8w NS3
-//   11: 256x128x64 8w(4x2) NS3
-//   20..22: staged loops of 256x256x64 8w / 256x128x64 4w / 128x128x64 4w
+// K step (bytes) of the DMA configurations 0..3.
+constexpr int kStepOfConfig[4] = {64, 128, 128, 64};
+
+// Tile configurations (halo_gemm_config in halo.h): macro tile M x N x K-step bytes, wavefronts, ring depth.
+//   0: 256x256x64  8 (2x4) NS4      1: 256x256x128 8 (2x4) NS2      2: 256x128x128 8 (4x2) NS3
+//   3: 128x128x64  4 (2x2) NS4      4: staged 128x128x64 (any K)
 template <bool TRANSB>
 hipError_t launch_by_shape(const GemmArgs& a, hipStream_t s) {
     auto tiles = [&](int bm, int bn) { return ((a.M + bm - 1) / bm) * ((a.N + bn - 1) / bn); };
-    int cfg = g_forced_config;
+    int cfg = a.config;
     if (cfg < 0) {
-        // Enough 256x256 tiles to fill the 256 CUs: largest tile, 128-byte K steps.  Otherwise halve the tile
-        // in N; small problems take 128x128 tiles.
-        if (TRANSB) cfg = tiles(256, 256) >= 200 ? 4 : (tiles(256, 128) >= 200 ? 8 : 2);
-        else cfg = tiles(256, 256) >= 200 ? 0 : 2;
-    }
-    // The DMA loop cannot zero-fill a K tail when both operands are K-contiguous.
-    const bool dma_ok = !TRANSB || (a.K % 128 == 0);
-    if (!dma_ok || cfg >= 20) {
-        switch (cfg >= 20 ? cfg - 20 : (cfg == 0 || cfg == 4 ? 0 : (cfg == 2 ? 2 : 1))) {
-            case 0: return launch_staged<256, 256, 64, 2, 4, TRANSB>(a, s);
-            case 1: return launch_staged<256, 128, 64, 2, 2, TRANSB>(a, s);
-            case 2: return launch_staged<128, 128, 64, 2, 2, TRANSB>(a, s);
-            default: return hipErrorInvalidValue;
-        }
+        // Enough 256x256 tiles to fill the 256 CUs: largest tile (128-byte K steps when both operands are
+        // K-contiguous).  Otherwise halve the tile in N; small problems take 128x128 tiles.  The DMA loops need whole
+        // K steps; a ragged K takes the staged loop.
+        if (TRANSB) cfg = tiles(256, 256) >= 200 ? 1 : (tiles(256, 128) >= 200 ? 2 : 3);
+        else cfg = tiles(256, 256) >= 200 ? 0 : 3;
+        if (a.K % kStepOfConfig[cfg] != 0) cfg = (a.K % 64 == 0) ? 3 : 4;
     }
     switch (cfg) {
         case 0: return launch_dma<256, 256, 64, 2, 4, TRANSB, 4>(a, s);
-        case 1: return launch_dma<256, 128, 64, 2, 4, TRANSB, 4>(a, s);
-        case 2: return launch_dma<128, 128, 64, 2, 2, TRANSB, 4>(a, s);
-        case 3: return launch_dma<128, 256, 64, 2, 4, TRANSB, 4>(a, s);
-        case 4: return launch_dma<256, 256, 128, 2, 4, TRANSB, 2>(a, s);
-        case 5: return launch_dma<256, 128, 128, 2, 4, TRANSB, 3>(a, s);
-        case 6: return launch_dma<256, 128, 128, 2, 2, TRANSB, 3>(a, s);
-        case 7: return launch_dma<128, 256, 128, 2, 4, TRANSB, 3>(a, s);
-        case 8: return launch_dma<256, 128, 128, 4, 2, TRANSB, 3>(a, s);
-        case 9: return launch_dma<128, 128, 64, 2, 2, TRANSB, 3>(a, s);
-        case 10: return launch_dma<128, 256, 64, 2, 4, TRANSB, 3>(a, s);
-        case 11: return launch_dma<256, 128, 64, 4, 2, TRANSB, 3>(a, s);
+        case 1: return launch_dma<256, 256, 128, 2, 4, TRANSB, 2>(a, s);
+        case 2: return launch_dma<256, 128, 128, 4, 2, TRANSB, 3>(a, s);
+        case 3: return launch_dma<128, 128, 64, 2, 2, TRANSB, 4>(a, s);
+        case 4: return launch_staged<TRANSB>(a, s);
         default: return hipErrorInvalidValue;
     }
 }
 
 }  // namespace
 
-void set_gemm_config(int cfg) {
-    // bit 8 of a non-negative value selects the register-transposing variant of the K-strided path
-    g_nn_transpose_in_lds = !(cfg >= 0 && (cfg & 0x100));
-    g_pair_backward = !(cfg >= 0 && (cfg & 0x200));
-    g_forced_config = cfg >= 0 ? (cfg & 0xFF) : cfg;
+bool gemm_config_valid(int cfg, int64_t K) {
+    if (cfg == -1 || cfg == 4) return true;
+    return cfg >= 0 && cfg <= 3 && K % kStepOfConfig[cfg] == 0;
 }
 
 // Two K-strided-B products in one launch (the two backward products of the layer).  Falls back to two launches when
 // the shapes do not allow the shared configuration.
 hipError_t launch_gemm_i8_pair(const GemmArgs& a1, const GemmArgs& a2, hipStream_t s) {
     const bool ok = !a1.transB && !a2.transB && a1.M > 0 && a1.N > 0 && a2.M > 0 && a2.N > 0 && a1.K > 0 && a2.K > 0 &&
-                    a1.K % 64 == 0 && a2.K % 64 == 0 && g_nn_transpose_in_lds && g_pair_backward;
+                    a1.K % 64 == 0 && a2.K % 64 == 0 && a1.config == a2.config &&
+                    (a1.config == -1 || a1.config == 0 || a1.config == 3);
     if (!ok) {
         hipError_t e = launch_gemm_i8(a1, s);
         return e != hipSuccess ? e : launch_gemm_i8(a2, s);
     }
     // 256x256 tiles: the E product alone would leave half the CUs idle at 2048 tokens, the pair fills them
     // (measured on config c2: 183-190 us per step against 197 with 128x128 tiles and 204 with two launches).
+    if (a1.config == 3) return launch_dma<128, 128, 64, 2, 2, false, 4>(a1, s, &a2);
     return launch_dma<256, 256, 64, 2, 4, false, 4>(a1, s, &a2);
 }
 
 hipError_t launch_gemm_i8(const GemmArgs& a, hipStream_t s) {
     if (a.M == 0 || a.N == 0) return hipSuccess;
     return a.transB ? launch_by_shape<true>(a, s) : launch_by_shape<false>(a, s);
+}
+
+hipError_t launch_mfma_i8_probe(const int8_t* operands, int iters, int32_t* sink, hipStream_t s) {
+    hipLaunchKernelGGL(mfma_i8_probe_kernel, dim3(256), dim3(512), 0, s, operands, iters, sink);
+    return hipGetLastError();
 }
 
 }  // namespace halo

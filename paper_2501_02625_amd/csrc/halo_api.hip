@@ -34,6 +34,8 @@ struct BwdWorkspace {
     size_t eq, s_e, eqt, s_g, amax, acc, acc_g, f32, total;
 };
 
+inline bool acc_fits_int32(int64_t k) { return 127ll * 127ll * k < (1ll << 31); }
+
 inline int32_t default_block(int64_t len, int64_t cap) {
     int64_t b = len & -len;
     if (b > cap) b = cap;
@@ -48,6 +50,9 @@ halo_status resolve_desc(const halo_linear_desc* d, int32_t* hm, int32_t* hb) {
     if (d->b > kMaxDim || d->m > kMaxDim || d->n > kMaxDim) return HALO_EUNSUPPORTED;
     if (d->b % 16 || d->m % 16 || d->n % 16) return HALO_ESHAPE;
     if (d->m > kMaxRowCols || d->n > kMaxRowCols) return HALO_EUNSUPPORTED;
+    // every one of b, m, n is the reduction length of one of the three products: the largest possible sum of
+    // products of codes, 127*127*K, must fit the int32 accumulator
+    if (!acc_fits_int32(d->b) || !acc_fits_int32(d->m) || !acc_fits_int32(d->n)) return HALO_ESHAPE;
     *hm = 0;
     *hb = 0;
     if (d->level >= 1) {
@@ -98,8 +103,6 @@ const char* halo_status_string(halo_status s) {
 }
 
 int halo_version(void) { return 1; }
-
-void halo_gemm_i8_set_config(int config) { set_gemm_config(config); }
 
 // ------------------------------------------------------------------------------------------------
 size_t halo_hadamard_quant_workspace_bytes(int64_t rows, int64_t cols, halo_axis axis, int32_t had_block_left) {
@@ -193,7 +196,7 @@ static halo_status check_gemm(const halo_gemm_desc* d, GemmArgs* out, bool* skip
     if (d->K > 0 && (!d->A || !d->B)) return HALO_EINVAL;
     if (d->M > kMaxDim || d->N > kMaxDim || d->K > kMaxDim) return HALO_EUNSUPPORTED;
     if (d->K % 16) return HALO_ESHAPE;
-    if (127ll * 127ll * d->K >= (1ll << 31)) return HALO_ESHAPE;
+    if (!acc_fits_int32(d->K)) return HALO_ESHAPE;
     if (d->K > 0) {
         if (d->lda < d->K || d->ldb < (d->transB ? d->K : d->N)) return HALO_ESHAPE;
         if (!aligned16(d->A) || !aligned16(d->B) || d->lda % 16 || d->ldb % 16) return HALO_EALIGN;
@@ -206,20 +209,35 @@ static halo_status check_gemm(const halo_gemm_desc* d, GemmArgs* out, bool* skip
         if (d->ld_acc < d->N) return HALO_ESHAPE;
         if (!aligned16(d->acc_out) || (d->ld_acc * 4) % 16) return HALO_EALIGN;
     }
+    if (d->config < HALO_GEMM_AUTO || d->config > HALO_GEMM_STAGED_128x128x64) return HALO_EINVAL;
+    if (!gemm_config_valid(d->config, d->K)) return HALO_ESHAPE;
     *out = GemmArgs{d->A, d->lda, d->B, d->ldb, d->transB ? 1 : 0, d->M, d->N, d->K, d->row_scale, d->col_scale, d->C,
-                    d->c_dt == HALO_F32 ? 1 : 0, d->ldc, d->acc_out, d->ld_acc};
+                    d->c_dt == HALO_F32 ? 1 : 0, d->ldc, d->acc_out, d->ld_acc, d->config};
     return HALO_OK;
 }
 
 halo_status halo_gemm_i8(const int8_t* A, int64_t lda, const int8_t* B, int64_t ldb, int transB, int64_t M,
                          int64_t N, int64_t K, const float* row_scale, const float* col_scale, void* C,
                          halo_dtype c_dt, int64_t ldc, int32_t* acc_out, int64_t ld_acc, void* stream) {
-    const halo_gemm_desc d{A, lda, B, ldb, transB, M, N, K, row_scale, col_scale, C, (int32_t)c_dt, ldc, acc_out, ld_acc};
-    GemmArgs g;
+    const halo_gemm_desc d{A, lda, B, ldb, transB, M, N, K, row_scale, col_scale, C, (int32_t)c_dt, ldc, acc_out, ld_acc,
+                           HALO_GEMM_AUTO};
+    return halo_gemm_i8_desc(&d, stream);
+}
+
+halo_status halo_gemm_i8_desc(const halo_gemm_desc* g, void* stream) {
+    if (!g) return HALO_EINVAL;
+    GemmArgs a;
     bool skip;
-    const halo_status st = check_gemm(&d, &g, &skip);
+    const halo_status st = check_gemm(g, &a, &skip);
     if (st != HALO_OK || skip) return st;
-    return from_hip(launch_gemm_i8(g, reinterpret_cast<hipStream_t>(stream)));
+    return from_hip(launch_gemm_i8(a, reinterpret_cast<hipStream_t>(stream)));
+}
+
+halo_status halo_mfma_i8_probe(const int8_t* operands, int32_t iters, int32_t* sink, void* stream) {
+    if (!operands || iters < 0) return HALO_EINVAL;
+    if (!aligned16(operands)) return HALO_EALIGN;
+    if (iters == 0) return HALO_OK;
+    return from_hip(launch_mfma_i8_probe(operands, iters, sink, reinterpret_cast<hipStream_t>(stream)));
 }
 
 halo_status halo_gemm_i8_pair(const halo_gemm_desc* g1, const halo_gemm_desc* g2, void* stream) {
@@ -370,9 +388,9 @@ halo_status halo_linear_bwd(const halo_linear_desc* desc, const void* E, const i
     // ---- the two products on the saved codes.  Level 0 scales and stores the result in the epilogue; levels 1, 2
     // leave int32 accumulators for the un-rotation.  When both are wanted they share one launch.
     GemmArgs gx{Eq, n, Wq, m, 0, b, m, n, level == 0 ? s_e : nullptr, nullptr, level == 0 ? EX : nullptr,
-                odt == HALO_F32 ? 1 : 0, m, level == 0 ? nullptr : acc, m};
+                odt == HALO_F32 ? 1 : 0, m, level == 0 ? nullptr : acc, m, HALO_GEMM_AUTO};
     GemmArgs gg{EqT, b, Xq, m, 0, n, m, b, level == 0 ? s_g : nullptr, nullptr, level == 0 ? G : nullptr,
-                odt == HALO_F32 ? 1 : 0, m, level == 0 ? nullptr : acc_g, m};
+                odt == HALO_F32 ? 1 : 0, m, level == 0 ? nullptr : acc_g, m, HALO_GEMM_AUTO};
     hipError_t he = hipSuccess;
     if (both) he = launch_gemm_i8_pair(gx, gg, hs);
     else if (EX) he = launch_gemm_i8(gx, hs);

@@ -98,11 +98,14 @@ struct GemmArgs {
     int64_t ldc;
     int32_t* acc_out;
     int64_t ld_acc;
+    int config;              // halo_gemm_config: -1 = chosen by shape
 };
 hipError_t launch_gemm_i8(const GemmArgs& a, hipStream_t s);
 hipError_t launch_gemm_i8_pair(const GemmArgs& a1, const GemmArgs& a2, hipStream_t s);
-// Tuning hook: force one macro-tile configuration (-1 = choose by shape).
-void set_gemm_config(int cfg);
+// True if `cfg` names a tile configuration that can run a product with reduction length K.
+bool gemm_config_valid(int cfg, int64_t K);
+// 256 workgroups x 8 wavefronts x iters x 16 MFMAs on the 4 KB of operand bytes at `operands`.
+hipError_t launch_mfma_i8_probe(const int8_t* operands, int iters, int32_t* sink, hipStream_t s);
 
 inline int ilog2_exact(int64_t v) {
     int l = 0;

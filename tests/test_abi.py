@@ -104,10 +104,20 @@ def test_gemm_argument_errors(lib):
 
 def test_gemm_pair_argument_errors(lib):
     A, B, C = 0x1000, 0x2000, 0x3000
-    good = binding.GemmDesc(A, 64, B, 64, 0, 32, 64, 64, None, None, C, binding.HALO_F32, 64, None, 0)
-    bad_k = binding.GemmDesc(A, 64, B, 64, 0, 32, 64, 40, None, None, C, binding.HALO_F32, 64, None, 0)
-    no_out = binding.GemmDesc(A, 64, B, 64, 0, 32, 64, 64, None, None, None, binding.HALO_F32, 64, None, 0)
-    empty = binding.GemmDesc(None, 0, None, 0, 0, 0, 64, 64, None, None, None, binding.HALO_F32, 0, None, 0)
+    good = binding.GemmDesc(A, 64, B, 64, 0, 32, 64, 64, None, None, C, binding.HALO_F32, 64, None, 0, -1)
+    bad_k = binding.GemmDesc(A, 64, B, 64, 0, 32, 64, 40, None, None, C, binding.HALO_F32, 64, None, 0, -1)
+    no_out = binding.GemmDesc(A, 64, B, 64, 0, 32, 64, 64, None, None, None, binding.HALO_F32, 64, None, 0, -1)
+    empty = binding.GemmDesc(None, 0, None, 0, 0, 0, 64, 64, None, None, None, binding.HALO_F32, 0, None, 0, -1)
+    bad_cfg = binding.GemmDesc(A, 64, B, 64, 0, 32, 64, 64, None, None, C, binding.HALO_F32, 64, None, 0, 7)
+    k_step = binding.GemmDesc(A, 64, B, 64, 0, 32, 64, 64, None, None, C, binding.HALO_F32, 64, None, 0, 1)   # K % 128
+    assert lib.halo_gemm_i8_desc(ctypes.byref(bad_cfg), None) == binding.HALO_EINVAL
+    assert lib.halo_gemm_i8_desc(ctypes.byref(k_step), None) == binding.HALO_ESHAPE
+    assert lib.halo_gemm_i8_desc(None, None) == binding.HALO_EINVAL
+    assert lib.halo_gemm_i8_desc(ctypes.byref(empty), None) == binding.HALO_OK
+    assert lib.halo_mfma_i8_probe(None, 1, None, None) == binding.HALO_EINVAL
+    assert lib.halo_mfma_i8_probe(ctypes.c_void_p(0x1000), -1, None, None) == binding.HALO_EINVAL
+    assert lib.halo_mfma_i8_probe(ctypes.c_void_p(0x1004), 1, None, None) == binding.HALO_EALIGN
+    assert lib.halo_mfma_i8_probe(ctypes.c_void_p(0x1000), 0, None, None) == binding.HALO_OK
     f = lib.halo_gemm_i8_pair
     assert f(None, ctypes.byref(good), None) == binding.HALO_EINVAL
     assert f(ctypes.byref(good), ctypes.byref(bad_k), None) == binding.HALO_ESHAPE
@@ -128,6 +138,12 @@ def test_linear_desc_errors_and_workspace(lib):
     assert lib.halo_linear_fwd(ctypes.byref(odd), P, P, P, P, P, P, P, None, 0, None) == binding.HALO_ESHAPE
     blk = binding.make_desc(64, 96, 64, 1, had_block_m=64)
     assert lib.halo_linear_fwd(ctypes.byref(blk), P, P, P, P, P, P, P, None, 0, None) == binding.HALO_ESHAPE
+    # tokens are the reduction length of G = E^T X: 127*127*b must fit the int32 accumulator (b <= 133,136)
+    long_b = binding.make_desc(133152, 64, 64, 1)
+    assert lib.halo_linear_fwd(ctypes.byref(long_b), P, P, P, P, P, P, P, None, 0, None) == binding.HALO_ESHAPE
+    assert lib.halo_linear_bwd(ctypes.byref(long_b), P, P, P, P, P, P, P, P, 1 << 40, None) == binding.HALO_ESHAPE
+    assert binding.halo_linear_workspace_bytes(long_b) == 0
+    assert binding.halo_linear_workspace_bytes(binding.make_desc(133136, 64, 64, 1)) > 0
     ok = binding.make_desc(64, 64, 64, 1)
     assert lib.halo_linear_fwd(ctypes.byref(ok), P, P, None, P, P, P, P, None, 0, None) == binding.HALO_EINVAL
     assert lib.halo_linear_bwd(ctypes.byref(ok), P, P, P, P, P, None, None, P, 1 << 30, None) == binding.HALO_EINVAL

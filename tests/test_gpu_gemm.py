@@ -10,15 +10,6 @@ from tests import gpu_util as gu
 pytestmark = pytest.mark.gpu
 
 
-@pytest.fixture(autouse=True, scope="module")
-def forced_config():
-    """HALO_TEST_GEMM_CFG=<n> runs this module with one GEMM tile configuration forced (development aid)."""
-    import os
-    cfg = int(os.environ.get("HALO_TEST_GEMM_CFG", "-1"))
-    binding.halo_gemm_i8_set_config(cfg)
-    yield
-    binding.halo_gemm_i8_set_config(-1)
-
 # M, N, K -- chosen to hit each macro-tile configuration, ragged edges and a K tail
 SHAPES = [
     (128, 512, 512),       # config c1 forward
@@ -31,6 +22,37 @@ SHAPES = [
     (4100, 3900, 80),      # 256x256 tiles with ragged edges
     (512, 14336, 64),
 ]
+
+
+# Every tile configuration on shapes its K step divides (ragged M and N, several trips through the ring), through
+# halo_gemm_i8_desc: the configurations differ in speed only.
+@pytest.mark.parametrize("name", sorted(binding.HALO_GEMM_CONFIGS))
+@pytest.mark.parametrize("trans_b", [True, False])
+def test_every_tile_configuration_gives_the_same_accumulators(name, trans_b):
+    cfg = binding.HALO_GEMM_CONFIGS[name]
+    rng = np.random.default_rng(cfg + 10 * int(trans_b))
+    M, N, K = 600, 520, 1024 + (16 if name.startswith("staged") else 0)
+    a = rand_codes(rng, (M, K))
+    b = rand_codes(rng, (N, K) if trans_b else (K, N))
+    ldb = (b.shape[1] + 15) // 16 * 16
+    bd = torch.zeros((b.shape[0], ldb), dtype=torch.int8, device=gu.DEV)
+    bd[:, :b.shape[1]] = gu.to_dev(b)
+    acc = torch.full((M, N), -7, dtype=torch.int32, device=gu.DEV)
+    binding.halo_gemm_i8_desc(binding.gemm_desc(gu.to_dev(a), bd[:, :b.shape[1]], trans_b=trans_b, acc_out=acc, config=cfg))
+    gu.assert_codes_equal(acc, orc.gemm_codes(a, b.T if trans_b else b), "accumulators, configuration " + name)
+
+
+def test_tile_configuration_argument_errors():
+    a = torch.zeros((64, 80), dtype=torch.int8, device=gu.DEV)
+    b = torch.zeros((64, 80), dtype=torch.int8, device=gu.DEV)
+    acc = torch.zeros((64, 64), dtype=torch.int32, device=gu.DEV)
+    with pytest.raises(binding.HaloError) as e:       # K = 80 is not a multiple of the 64-byte K step
+        binding.halo_gemm_i8_desc(binding.gemm_desc(a, b, trans_b=True, acc_out=acc, config=0))
+    assert e.value.status == binding.HALO_ESHAPE
+    with pytest.raises(binding.HaloError) as e:
+        binding.halo_gemm_i8_desc(binding.gemm_desc(a, b, trans_b=True, acc_out=acc, config=9))
+    assert e.value.status == binding.HALO_EINVAL
+    binding.halo_gemm_i8_desc(binding.gemm_desc(a, b, trans_b=True, acc_out=acc, config=4))
 
 
 def rand_codes(rng, shape, extreme=False):
@@ -137,3 +159,48 @@ def test_gemm_pair_matches_two_single_launches():
                               binding.gemm_desc(dEqT, dXq, trans_b=False, acc_out=acc2))
     gu.assert_codes_equal(acc1, orc.gemm_codes(a, bb.T), "fallback pair, first")
     gu.assert_codes_equal(acc2, orc.gemm_codes(EqT, Xq), "fallback pair, second")
+
+
+# Full-size products of configs c2 and c3 in the tile configuration the library picks for them: the steady state of
+# the global->LDS ring (64..224 trips) on the large macro tiles.  Each runs twice into separate buffers: same bits
+# both times, and the oracle's bits.
+FULL = [
+    ("c2 forward", 2048, 4096, 4096, True),
+    ("c3 forward", 4096, 4096, 14336, True),
+    ("c2 E_X", 2048, 4096, 4096, False),
+    ("c2 G", 4096, 4096, 2048, False),
+    ("c3 E_X / G", 4096, 14336, 4096, False),
+]
+
+
+@pytest.mark.parametrize("what,M,N,K,trans_b", FULL, ids=[f[0] for f in FULL])
+def test_gemm_full_size_accumulators_bit_exact_and_repeatable(what, M, N, K, trans_b):
+    rng = np.random.default_rng(M + 3 * N + 7 * K + int(trans_b))
+    a = rand_codes(rng, (M, K))
+    b = rand_codes(rng, (N, K) if trans_b else (K, N))
+    da, db = gu.to_dev(a), gu.to_dev(b)
+    _, acc1 = binding.halo_gemm_i8(da, db, trans_b=trans_b, out_dtype=None, want_acc=True)
+    _, acc2 = binding.halo_gemm_i8(da, db, trans_b=trans_b, out_dtype=None, want_acc=True)
+    assert torch.equal(acc1, acc2), "two runs of the same product differ"
+    del acc2
+    gu.assert_codes_equal(acc1, orc.gemm_codes(a, b.T if trans_b else b), what + " accumulators")
+
+
+@pytest.mark.parametrize("b,m,n", [(2048, 4096, 4096), (4096, 14336, 4096)], ids=["c2", "c3"])
+def test_gemm_pair_full_size_bit_exact_and_repeatable(b, m, n):
+    """The paired backward launch at the sizes of configs c2 and c3: E_X = Eq Wq and G = EqT Xq accumulators."""
+    rng = np.random.default_rng(b + m + n)
+    Eq = rand_codes(rng, (b, n)); Wq = rand_codes(rng, (n, m)); EqT = rand_codes(rng, (n, b)); Xq = rand_codes(rng, (b, m))
+    dEq, dWq, dEqT, dXq = map(gu.to_dev, (Eq, Wq, EqT, Xq))
+    accs = []
+    for _ in range(2):
+        ax = torch.empty((b, m), dtype=torch.int32, device=gu.DEV)
+        ag = torch.empty((n, m), dtype=torch.int32, device=gu.DEV)
+        binding.halo_gemm_i8_pair(binding.gemm_desc(dEq, dWq, trans_b=False, acc_out=ax),
+                                  binding.gemm_desc(dEqT, dXq, trans_b=False, acc_out=ag))
+        accs.append((ax, ag))
+    assert torch.equal(accs[0][0], accs[1][0]) and torch.equal(accs[0][1], accs[1][1]), "two runs differ"
+    ax, ag = accs[0]
+    del accs
+    gu.assert_codes_equal(ax, orc.gemm_codes(Eq, Wq), "paired E_X accumulators")
+    gu.assert_codes_equal(ag, orc.gemm_codes(EqT, Xq), "paired G accumulators")

@@ -1,7 +1,8 @@
 """GPU parity of the whole layer (halo_linear_fwd / halo_linear_bwd) against the CPU oracle, through the C ABI.
 
-Bars: saved INT8 codes and fp32 scales bit-exact; fp32 outputs within 1e-3 relative (max-abs and Frobenius);
-bf16 outputs within one bf16 ulp of the rounded oracle value."""
+Bars: saved INT8 codes, fp32 scales and int32 accumulators bit-exact; fp32 outputs bit-identical to the oracle's
+(well inside the 1e-3 relative bar the build target states); bf16 outputs within one bf16 ulp of the rounded
+oracle value."""
 import numpy as np
 import pytest
 import torch
@@ -13,7 +14,31 @@ from tests import gpu_util as gu
 pytestmark = pytest.mark.gpu
 
 
-def run_and_check(b, m, n, level, Xb, Wb, Eb, odt=torch.float32, hm=0, hb=0, state=None, check_fwd=True):
+def check_internals(b, m, n, level, hb_eff, E, st, f, ex, g):
+    """The intermediate tensors of the layer at this size, through the entry points the layer itself uses:
+    forward accumulators, both quantisations of E, both backward accumulators (one paired launch)."""
+    _, acc = binding.halo_gemm_i8(st.Xq, st.Wq, trans_b=True, out_dtype=None, want_acc=True)
+    gu.assert_codes_equal(acc, f["acc"], "forward accumulators")
+    del acc
+    if level <= 1:
+        Eq, s_e, EqT, s_g = binding.halo_quant_dual(E, fold_cols=st.s_w, fold_rows=st.s_x)
+    else:
+        Eq, s_e = binding.halo_hadamard_quant(E, had_block_left=hb_eff, fold=st.s_w)
+        EqT, s_g = binding.halo_hadamard_quant(E, axis=binding.HALO_QUANT_COLS_T, fold=st.s_x)
+    gu.assert_codes_equal(Eq, ex["Eq"], "Eq"); gu.assert_f32_identical(s_e, ex["s_e"], "s_e")
+    gu.assert_codes_equal(EqT, g["EqT"], "EqT"); gu.assert_f32_identical(s_g, g["s_g"], "s_g")
+    acc_x = torch.empty((b, m), dtype=torch.int32, device=gu.DEV)
+    acc_g = torch.empty((n, m), dtype=torch.int32, device=gu.DEV)
+    binding.halo_gemm_i8_pair(binding.gemm_desc(Eq, st.Wq, trans_b=False, acc_out=acc_x),
+                              binding.gemm_desc(EqT, st.Xq, trans_b=False, acc_out=acc_g))
+    gu.assert_codes_equal(acc_x, ex["acc"], "E_X accumulators")
+    gu.assert_codes_equal(acc_g, g["acc"], "G accumulators")
+
+
+def run_and_check(b, m, n, level, Xb, Wb, Eb, odt=torch.float32, hm=0, hb=0, state=None, check_fwd=True,
+                  internals=False):
+    """Saved codes and scales bit-exact; fp32 outputs bit-identical to the oracle's (the kernels keep its stage
+    order and its order of multiplications; +0 and -0 compare equal); bf16 outputs within one bf16 ulp."""
     desc = binding.make_desc(b, m, n, level, odt, hm, hb)
     hm_eff = hm or min(m & -m, 4096)
     hb_eff = hb or (b & -b)
@@ -22,7 +47,7 @@ def run_and_check(b, m, n, level, Xb, Wb, Eb, odt=torch.float32, hm=0, hb=0, sta
     f = orc.forward(orc.bf16_bits_to_real(Xb), orc.bf16_bits_to_real(Wb), level, hm_eff)
     gu.assert_codes_equal(st.Xq, f["Xq"], "Xq"); gu.assert_f32_identical(st.s_x, f["s_x"], "s_x")
     gu.assert_codes_equal(st.Wq, f["Wq"], "Wq"); gu.assert_f32_identical(st.s_w, f["s_w"], "s_w")
-    cmp = gu.assert_close_1e3 if odt == torch.float32 else gu.assert_bf16_within_one_ulp
+    cmp = gu.assert_f32_identical if odt == torch.float32 else gu.assert_bf16_within_one_ulp
     if check_fwd:
         cmp(Y, f["Y"], "Y")
     if Eb is None:
@@ -32,9 +57,12 @@ def run_and_check(b, m, n, level, Xb, Wb, Eb, odt=torch.float32, hm=0, hb=0, sta
     Er = orc.bf16_bits_to_real(Eb)
     ex = orc.backward_input(Er, f["Wq"], f["s_w"], level, hm_eff, hb_eff)
     cmp(EX, ex["EX"], "E_X")
-    del ex
+    ex.pop("EX"); del EX
     g = orc.backward_weight(Er, f["Xq"], f["s_x"], level, hm_eff)
     cmp(G, g["G"], "G")
+    g.pop("G"); del G
+    if internals:
+        check_internals(b, m, n, level, hb_eff, E, st, f, ex, g)
     return st
 
 
@@ -99,7 +127,7 @@ def test_config_c2_full_size_level1():
     """Config c2 (the benchmarked workload): tokens 2048, 4096 x 4096, HALO-1, every output compared in full."""
     cfg = inputs.CONFIGS["c2"]
     t = inputs.make_linear_inputs(cfg)
-    run_and_check(cfg.tokens, 4096, 4096, cfg.level, t["X"], t["W"], t["E"], odt=torch.float32)
+    run_and_check(cfg.tokens, 4096, 4096, cfg.level, t["X"], t["W"], t["E"], odt=torch.float32, internals=True)
     run_and_check(cfg.tokens, 4096, 4096, cfg.level, t["X"], t["W"], t["E"], odt=torch.bfloat16)
 
 
@@ -107,7 +135,7 @@ def test_config_c3_full_size_level2():
     """Config c3: tokens 4096, K = 14336 = 7 x 2048 block-diagonal, N = 4096, HALO-2, compared in full."""
     cfg = inputs.CONFIGS["c3"]
     t = inputs.make_linear_inputs(cfg)
-    run_and_check(cfg.tokens, 14336, 4096, cfg.level, t["X"], t["W"], t["E"], odt=torch.float32)
+    run_and_check(cfg.tokens, 14336, 4096, cfg.level, t["X"], t["W"], t["E"], odt=torch.float32, internals=True)
 
 
 def test_config_c4_decoder_layer_linears_level2():
@@ -136,8 +164,8 @@ def test_config_c4_decoder_layer_linears_level2():
         states[lin.name] = st
         hm = min(lin.m & -lin.m, 4096)
         f = orc.forward(orc.bf16_bits_to_real(Xb), orc.bf16_bits_to_real(Wb), cfg.level, hm)
-        gu.assert_codes_equal(st.Xq, f["Xq"], lin.name + " Xq")
-        gu.assert_codes_equal(st.Wq, f["Wq"], lin.name + " Wq")
+        gu.assert_codes_equal(st.Xq, f["Xq"], lin.name + " Xq"); gu.assert_f32_identical(st.s_x, f["s_x"], lin.name + " s_x")
+        gu.assert_codes_equal(st.Wq, f["Wq"], lin.name + " Wq"); gu.assert_f32_identical(st.s_w, f["s_w"], lin.name + " s_w")
         gu.assert_bf16_within_one_ulp(Y, f["Y"], lin.name + " Y")
         EX, G = binding.halo_linear_bwd(desc, gu.bits_to_dev(Eb), st)
         Er = orc.bf16_bits_to_real(Eb)

@@ -284,7 +284,8 @@ def test_levels_equal_plain_products_when_rounding_is_off(level, shape):
 
 
 def test_planted_mistakes_are_caught_by_the_algebra_pin():
-    """The pin above has teeth: dropping the fold, an un-rotation or the left Hadamard breaks it."""
+    """The pin above has teeth: dropping the fold or an un-rotation breaks it.  (The left Hadamard of level 2 cancels
+    in the product; test_level2_really_left_rotates_the_error_before_quantising pins it.)"""
     rng = np.random.default_rng(11)
     b, m, n = 32, 64, 48
     X = rng.standard_normal((b, m)); W = rng.standard_normal((n, m)) * rng.lognormal(0, 1, size=(n, 1))
@@ -298,6 +299,54 @@ def test_planted_mistakes_are_caught_by_the_algebra_pin():
     assert np.max(np.abs(lvl_mismatch - ref["EX"])) > 1e-3 * np.max(np.abs(ref["EX"]))
     g_wrong = orc.backward_weight(E, f["Xq"], f["s_x"], 0, m, rounding=False, real=np.float64)["G"]
     assert np.max(np.abs(g_wrong - ref["G"])) > 1e-3 * np.max(np.abs(ref["G"]))
+
+
+def _level2_quantises_the_left_rotated_error(backward_input, E, Wq, s_w, m, b, hb):
+    """True iff backward_input(level 2)'s quantiser input is (I (x) H_hb)^T E scaled by s_w per column, built here
+    from the dense closed-form matrix: with the rounding off, Eq * s_e is exactly the tensor that was quantised."""
+    L = np.kron(np.eye(b // hb), dense_hadamard(hb))
+    want = (L.T @ E) * s_w[None, :]
+    r = backward_input(E, Wq, s_w, 2, m, hb)
+    got = r["Eq"] * r["s_e"][:, None]
+    return got.shape == want.shape and np.max(np.abs(got - want)) <= 1e-12 * np.max(np.abs(want))
+
+
+@pytest.mark.parametrize("hb", [32, 8])
+def test_level2_really_left_rotates_the_error_before_quantising(hb):
+    """Table "HALO levels", HALO-2 row: E = H^T (H E_Y)_Q (WH)_Q H^T.  The two left-hand rotations cancel
+    when Q is a pure rescale, so the product pin above cannot see them; this one looks at what is quantised."""
+    rng = np.random.default_rng(21)
+    b, m, n = 32, 64, 48
+    X = rng.standard_normal((b, m)); W = rng.standard_normal((n, m)) * rng.lognormal(0, 1, size=(n, 1))
+    E = rng.standard_t(3, size=(b, n))
+    f = orc.forward(X, W, 2, m, rounding=False, real=np.float64)
+    oracle = lambda E_, Wq, s_w, lvl, m_, hb_: orc.backward_input(E_, Wq, s_w, lvl, m_, hb_, rounding=False, real=np.float64)
+    assert _level2_quantises_the_left_rotated_error(oracle, E, f["Wq"], f["s_w"], m, b, hb)
+    # planted mistakes: level 2 computed as level 1, level 2 with the left rotation skipped, with a left block
+    # of the wrong size, and with the rotation on the wrong (right-hand) side of E
+    as_level1 = lambda E_, Wq, s_w, lvl, m_, hb_: oracle(E_, Wq, s_w, 1, m_, hb_)
+    no_left = lambda E_, Wq, s_w, lvl, m_, hb_: oracle(E_, Wq, s_w, 2, m_, 0)
+    wrong_block = lambda E_, Wq, s_w, lvl, m_, hb_: oracle(E_, Wq, s_w, 2, m_, hb_ // 2)
+    right_side = lambda E_, Wq, s_w, lvl, m_, hb_: oracle(orc.fwht(E_, 16, 1), Wq, s_w, 1, m_, hb_)
+    for mutant in (as_level1, no_left, wrong_block, right_side):
+        assert not _level2_quantises_the_left_rotated_error(mutant, E, f["Wq"], f["s_w"], m, b, hb)
+    # and the level-1 quantiser input is the plain E (x) s_w: the two levels differ exactly by L
+    r1 = oracle(E, f["Wq"], f["s_w"], 1, m, hb)
+    assert np.allclose(r1["Eq"] * r1["s_e"][:, None], E * f["s_w"][None, :], rtol=1e-12, atol=0)
+    r2 = oracle(E, f["Wq"], f["s_w"], 2, m, hb)
+    assert np.max(np.abs(r2["Eq"] * r2["s_e"][:, None] - r1["Eq"] * r1["s_e"][:, None])) > 1e-3 * np.max(np.abs(E * f["s_w"]))
+    # with the rounding on (fp32), the INT8 codes are those of the dense-matrix rotation up to one code step at
+    # values that fp32 and fp64 place on different sides of a rounding boundary
+    E32 = E.astype(np.float32)
+    f32 = orc.forward(X.astype(np.float32), W.astype(np.float32), 2, m)
+    got = orc.backward_input(E32, f32["Wq"], f32["s_w"], 2, m, hb)
+    L = np.kron(np.eye(b // hb), dense_hadamard(hb))
+    ref = (L.T @ E32.astype(np.float64)) * f32["s_w"].astype(np.float64)[None, :]
+    ref_codes = np.rint(ref * (127.0 / np.max(np.abs(ref), axis=1))[:, None])
+    d = np.abs(got["Eq"].astype(np.int64) - ref_codes.astype(np.int64))
+    assert d.max() <= 1 and np.mean(d != 0) < 0.01
+    as1 = orc.backward_input(E32, f32["Wq"], f32["s_w"], 1, m, hb)
+    assert np.mean(as1["Eq"] != got["Eq"]) > 0.5
 
 
 def test_fold_reduces_to_scalar_scale_formula_when_all_row_scales_are_equal():
