@@ -109,6 +109,20 @@ halo_status halo_quant_dual(const void* in, int64_t rows, int64_t cols, int64_t 
                             int8_t* out_qT, int64_t ld_qT, float* col_scale, void* workspace,
                             size_t workspace_bytes, void* stream);
 
+/* halo_quant_dual for callers that cannot allocate or bring a workspace: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same arguments (minus the workspace), same kernels and bit-identical
+ * results; the partial maxima live in an array built into the library
+ * (halo_quant_dual_static_max_workspace_bytes() bytes, 8 MiB, one copy per GPU, held until the process ends).  The
+ * call allocates nothing and frees nothing.  Sizes whose halo_quant_dual_workspace_bytes(rows, cols) exceeds that
+ * array are refused with HALO_EWORKSPACE.  All calls on one GPU share the array: calls that may overlap in time on one
+ * GPU (different streams, different host threads) race and must be serialised by the caller; halo_quant_dual with
+ * separate workspaces has no such restriction. */
+size_t halo_quant_dual_static_max_workspace_bytes(void);
+
+halo_status halo_quant_dual_static(const void* in, int64_t rows, int64_t cols, int64_t ld_in, const float* fold_cols,
+                                   const float* fold_rows, int8_t* out_q, int64_t ld_q, float* row_scale,
+                                   int8_t* out_qT, int64_t ld_qT, float* col_scale, void* stream);
+
 /* ---------------------------------------------------------------------------------------------
  * halo_gemm_i8: INT8 GEMM with int32 accumulation and a scaling epilogue.   (Section 2, Eqs. 1a-1c on
  * quantised operands; Table "HALO levels".)

@@ -26,6 +26,7 @@ EXPORTED_SYMBOLS = (
     "halo_status_string", "halo_version",
     "halo_hadamard_quant_workspace_bytes", "halo_hadamard_quant",
     "halo_quant_dual_workspace_bytes", "halo_quant_dual",
+    "halo_quant_dual_static_max_workspace_bytes", "halo_quant_dual_static",
     "halo_gemm_i8", "halo_gemm_i8_desc", "halo_gemm_i8_pair", "halo_mfma_i8_probe",
     "halo_dequant_unrotate_workspace_bytes", "halo_dequant_unrotate",
     "halo_linear_workspace_bytes", "halo_linear_fwd", "halo_linear_bwd",
@@ -80,6 +81,10 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.halo_quant_dual_workspace_bytes.argtypes = [i64, i64]
     lib.halo_quant_dual.restype = c.c_int
     lib.halo_quant_dual.argtypes = [vp, i64, i64, i64, vp, vp, vp, i64, vp, vp, i64, vp, vp, sz, vp]
+    lib.halo_quant_dual_static_max_workspace_bytes.restype = sz
+    lib.halo_quant_dual_static_max_workspace_bytes.argtypes = []
+    lib.halo_quant_dual_static.restype = c.c_int
+    lib.halo_quant_dual_static.argtypes = [vp, i64, i64, i64, vp, vp, vp, i64, vp, vp, i64, vp, vp]
     lib.halo_gemm_i8.restype = c.c_int
     lib.halo_gemm_i8.argtypes = [vp, i64, vp, i64, c.c_int, i64, i64, i64, vp, vp, vp, c.c_int, i64, vp, i64, vp]
     lib.halo_gemm_i8_pair.restype = c.c_int
@@ -197,6 +202,19 @@ def halo_quant_dual(x: torch.Tensor, *, fold_cols: Optional[torch.Tensor] = None
                              _ptr(workspace), workspace.numel(), _stream())
     _check(st, "halo_quant_dual")
     return out_q, row_scale, out_qt, col_scale
+
+
+def halo_quant_dual_static(x: torch.Tensor, *, fold_cols: Optional[torch.Tensor], fold_rows: Optional[torch.Tensor],
+                           out_q: torch.Tensor, row_scale: torch.Tensor, out_qt: torch.Tensor,
+                           col_scale: torch.Tensor) -> None:
+    """halo_quant_dual without a workspace and without any allocation: every output is passed in."""
+    _need_cuda(x, fold_cols, fold_rows, out_q, row_scale, out_qt, col_scale)
+    assert x.dim() == 2 and x.stride(1) == 1 and x.dtype == torch.bfloat16
+    rows, cols = x.shape
+    st = load_library().halo_quant_dual_static(_ptr(x), rows, cols, x.stride(0), _ptr(fold_cols), _ptr(fold_rows),
+                                               _ptr(out_q), out_q.stride(0), _ptr(row_scale), _ptr(out_qt),
+                                               out_qt.stride(0), _ptr(col_scale), _stream())
+    _check(st, "halo_quant_dual_static")
 
 
 def halo_gemm_i8(a: torch.Tensor, b: torch.Tensor, *, trans_b: bool, row_scale: Optional[torch.Tensor] = None,

@@ -6,10 +6,17 @@
 //   * the dual quantiser: row-wise codes (E_Y)_Q and transposed column-wise codes (E_Y^T)_Q from one tiling of E.
 #pragma clang fp contract(off)
 
+#include <mutex>
+
 #include "halo_internal.h"
 
 namespace halo {
 namespace {
+
+// Scratch of the allocation-free dual quantiser (halo_quant_dual_static): partial maxima of pass 1.  One copy per GPU
+// the library runs on, held until the process ends.  Host code never uses this name as an address: it asks the runtime
+// for the device address once per device (static_scratch_address) and passes that to the kernels.
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
 __device__ __forceinline__ uint32_t f32_to_bf16_rne(float f) {
     const uint32_t u = __float_as_uint(f);
@@ -534,6 +541,37 @@ hipError_t launch_dual_quant(const DualQuantArgs& a, hipStream_t s) {
     hipLaunchKernelGGL(dual_quant_kernel, grid, dim3(256), 0, s, in, a.ld_in, a.rows, a.cols, a.fold_c, a.fold_r, row_part,
                        col_part, (int)col_tiles, (int)row_tiles, a.out_q, a.ld_q, a.row_scale, a.out_qt, a.ld_qt, a.col_scale);
     return hipGetLastError();
+}
+
+// Device address of `scratch` on the current device, looked up on the first call for that device and kept.
+hipError_t static_scratch_address(void** out) {
+    constexpr int kMaxDevices = 64;
+    static std::mutex mu;
+    static void* address[kMaxDevices] = {};
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!address[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        address[dev] = p;
+    }
+    *out = address[dev];
+    return hipSuccess;
+}
+
+hipError_t launch_dual_quant_static(DualQuantArgs a, hipStream_t s) {
+    if (a.rows == 0 || a.cols == 0) return hipSuccess;
+    if (dual_quant_workspace_floats(a.rows, a.cols) * sizeof(float) > kStaticScratchBytes) return hipErrorInvalidValue;
+    void* p = nullptr;
+    hipError_t e = static_scratch_address(&p);
+    if (e != hipSuccess) return e;
+    a.amax_ws = reinterpret_cast<float*>(p);     // every entry pass 2 reads is written by pass 1 first: nothing to clear
+    return launch_dual_quant(a, s);
 }
 
 hipError_t launch_col_quant_t(const ColQuantArgs& a, hipStream_t s) {

@@ -185,6 +185,24 @@ halo_status halo_quant_dual(const void* in, int64_t rows, int64_t cols, int64_t 
     return from_hip(launch_dual_quant(dq, reinterpret_cast<hipStream_t>(stream)));
 }
 
+size_t halo_quant_dual_static_max_workspace_bytes(void) { return kStaticScratchBytes; }
+
+halo_status halo_quant_dual_static(const void* in, int64_t rows, int64_t cols, int64_t ld_in, const float* fold_cols,
+                                   const float* fold_rows, int8_t* out_q, int64_t ld_q, float* row_scale,
+                                   int8_t* out_qT, int64_t ld_qT, float* col_scale, void* stream) {
+    if (rows < 0 || cols < 0) return HALO_EINVAL;
+    if (rows == 0 || cols == 0) return HALO_OK;
+    if (!in || !out_q || !row_scale || !out_qT || !col_scale) return HALO_EINVAL;
+    if (rows > kMaxDim || cols > kMaxDim) return HALO_EUNSUPPORTED;
+    if (ld_in < cols || ld_q < cols || ld_qT < rows) return HALO_ESHAPE;
+    if (!aligned16(in) || !aligned16(out_q) || !aligned16(out_qT) || (ld_in * 2) % 16 || ld_q % 16 || ld_qT % 16)
+        return HALO_EALIGN;
+    // the partial maxima of this size must fit the built-in scratch array
+    if (halo_quant_dual_workspace_bytes(rows, cols) > kStaticScratchBytes) return HALO_EWORKSPACE;
+    DualQuantArgs dq{in, ld_in, rows, cols, fold_cols, fold_rows, out_q, ld_q, row_scale, out_qT, ld_qT, col_scale, nullptr};
+    return from_hip(launch_dual_quant_static(dq, reinterpret_cast<hipStream_t>(stream)));
+}
+
 // ------------------------------------------------------------------------------------------------
 // Argument check shared by halo_gemm_i8 and halo_gemm_i8_pair.  *skip is set when the product is empty (a no-op).
 static halo_status check_gemm(const halo_gemm_desc* d, GemmArgs* out, bool* skip) {

@@ -82,6 +82,10 @@ struct DualQuantArgs {
 };
 size_t dual_quant_workspace_floats(int64_t rows, int64_t cols);
 hipError_t launch_dual_quant(const DualQuantArgs& a, hipStream_t s);
+// The same with the partial maxima in a file-scope device array instead of a.amax_ws (which is ignored): no allocation,
+// no workspace argument.  Sizes whose partial maxima exceed kStaticScratchBytes are refused by the caller.
+constexpr size_t kStaticScratchBytes = size_t(8) << 20;
+hipError_t launch_dual_quant_static(DualQuantArgs a, hipStream_t s);
 
 // ---- INT8 GEMM ----
 struct GemmArgs {
