@@ -209,6 +209,63 @@ def test_quantizer_no_rounding_mode_is_a_pure_rescale():
     np.testing.assert_allclose(np.max(np.abs(c), axis=1), 127.0, rtol=1e-14)
 
 
+def test_quantize_tensor_hand_example_and_reduction_to_rows():
+    """One scale for the whole tensor (Section 4 setup).  Hand example; and when every row has the same absmax the
+    per-tensor quantizer must give exactly what the per-row one gives."""
+    v = np.array([[1.0, -2.0, 0.5, 4.0], [0.25, 0.0, -1.0, 3.0]], dtype=np.float32)
+    codes, scale = orc.quantize_tensor(v)
+    # 127/4 = 31.75: 1 -> 31.75 -> 32, -2 -> -63.5 -> -64 (tie to even), 0.5 -> 15.875 -> 16, 0.25 -> 7.9375 -> 8, 3 -> 95.25 -> 95
+    want = [[32, -64, 16, 127], [8, 0, -32, 95]]
+    assert codes.tolist() == want and codes.dtype == np.int8
+    assert scale.tolist() == [float(np.float32(4) / np.float32(127))] * 2 and scale.dtype == np.float32
+    # per-row would scale the second row by 127/3 instead
+    rows_codes, rows_scale = orc.quantize_rows(v)
+    assert rows_codes[0].tolist() == want[0] and rows_codes[1].tolist() != want[1]
+    rng = np.random.default_rng(31)
+    u = rng.standard_normal((9, 40)).astype(np.float32)
+    u[:, 0] = 5.0 * rng.choice([-1.0, 1.0], size=9)          # the same absmax in every row
+    ct, st = orc.quantize_tensor(u)
+    cr, sr = orc.quantize_rows(u)
+    assert np.array_equal(ct, cr) and np.array_equal(st, sr)
+    z, sz = orc.quantize_tensor(np.zeros((3, 4), dtype=np.float32))
+    assert not z.any() and sz.tolist() == [1.0, 1.0, 1.0]
+
+
+@pytest.mark.parametrize("level", [0, 1, 2])
+def test_per_tensor_levels_equal_plain_products_when_rounding_is_off(level):
+    """The paper-literal scalar-scale formulas of Table "HALO levels": with Q a pure rescale they reproduce
+    X W^T, E W and E^T X at every level (scales factor out, no fold)."""
+    rng = np.random.default_rng(40 + level)
+    b, m, n = 32, 64, 48
+    X = rng.standard_normal((b, m)); W = rng.standard_normal((n, m)) * 0.02; E = rng.standard_t(3, size=(b, n)) * 1e-3
+    f = orc.forward(X, W, level, m, rounding=False, real=np.float64, per_tensor=True)
+    ex = orc.backward_input(E, f["Wq"], f["s_w"], level, m, b, rounding=False, real=np.float64, per_tensor=True)
+    g = orc.backward_weight(E, f["Xq"], f["s_x"], level, m, rounding=False, real=np.float64, per_tensor=True)
+    ref = orc.plain_products(X, W, E)
+    for got, want in ((f["Y"], ref["Y"]), (ex["EX"], ref["EX"]), (g["G"], ref["G"])):
+        assert np.max(np.abs(got - want)) <= 1e-11 * np.max(np.abs(want))
+    assert np.all(f["s_x"] == f["s_x"][0]) and np.all(f["s_w"] == f["s_w"][0])
+    # the quantised error is E itself (left-rotated at level 2) over one scalar, not a folded tensor
+    L = dense_hadamard(b) if level >= 2 else np.eye(b)
+    assert np.allclose(ex["Eq"] * ex["s_e"][:, None], L.T @ E, rtol=1e-10, atol=1e-18)
+    assert np.all(ex["s_e"] == ex["s_e"][0])
+
+
+def test_per_tensor_is_worse_than_per_row_on_outlier_rows():
+    """Why the build target asks for per-row scales: with heavy-tailed errors one tensor-wide scale wastes most of
+    the INT8 range on a few rows (Section 3.2, Step 3 describes those outliers)."""
+    X = inputs.bf16_bits_to_f32(inputs.make_activations(128, 512, 0.005, 0))
+    W = inputs.bf16_bits_to_f32(inputs.make_weights(256, 512, 0))
+    E = inputs.bf16_bits_to_f32(inputs.make_errors(128, 256, 0))
+    ref = orc.plain_products(X, W, E)
+    err = {}
+    for pt in (False, True):
+        f = orc.forward(X, W, 1, 512, per_tensor=pt)
+        ex = orc.backward_input(E, f["Wq"], f["s_w"], 1, 512, 128, per_tensor=pt)
+        err[pt] = np.linalg.norm(ex["EX"].astype(np.float64) - ref["EX"]) / np.linalg.norm(ref["EX"])
+    assert err[True] > 1.5 * err[False] and err[False] < 0.1, err
+
+
 # ----------------------------------------------------------------------------- O3 / O4: GEMM, dequant
 def test_gemm_codes_brute_force_int64():
     rng = np.random.default_rng(7)
