@@ -49,6 +49,9 @@ typedef enum {
 
 typedef enum { HALO_BF16 = 0, HALO_F32 = 1 } halo_dtype;
 typedef enum { HALO_LEVEL0 = 0, HALO_LEVEL1 = 1, HALO_LEVEL2 = 2 } halo_level;
+/* Granularity of the symmetric absmax scales: one per row of the GEMM operand (this library's default), or one per
+ * tensor, the quantiser the paper itself uses (Section 4 setup; Appendix "HALO Levels for FFT"). */
+typedef enum { HALO_SCALE_PER_ROW = 0, HALO_SCALE_PER_TENSOR = 1 } halo_scale_mode;
 
 typedef enum {
     HALO_QUANT_ROWS = 0,    /* one scale per row of `in`; codes keep the layout of `in`            */
@@ -90,6 +93,22 @@ halo_status halo_hadamard_quant(const void* in, halo_dtype in_dt, int64_t rows, 
                                 int32_t had_block_left, const float* fold, int8_t* out_q,
                                 int64_t ld_q, float* out_scale, void* workspace,
                                 size_t workspace_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * halo_hadamard_quant_tensor: rotate -> absmax of the WHOLE tensor -> INT8, the paper's quantiser (Section 4 setup:
+ * "tensor-wise symmetric quantization"; Table "HALO levels").  Arguments as in halo_hadamard_quant, without a fold
+ * (a scalar scale factors out of the integer sums, so nothing has to be folded in):
+ *      amax = max |rotate(in)|;   codes = rint(rotate(in) * (127/amax));   scale = amax/127  (amax == 0: codes 0, scale 1)
+ * out_scale receives that one scale in EVERY entry (rows entries for HALO_QUANT_ROWS, cols for HALO_QUANT_COLS_T), so
+ * that every consumer of per-row scales works unchanged.  Two passes over the input (absmax, then quantise):
+ * 2 + 2 bytes read and 1 byte written per element.  Workspace: halo_hadamard_quant_tensor_workspace_bytes(...).
+ */
+size_t halo_hadamard_quant_tensor_workspace_bytes(int64_t rows, int64_t cols, halo_axis axis, int32_t had_block_left);
+
+halo_status halo_hadamard_quant_tensor(const void* in, halo_dtype in_dt, int64_t rows, int64_t cols, int64_t ld_in,
+                                       halo_axis axis, int32_t had_block, int32_t had_block_left, int8_t* out_q,
+                                       int64_t ld_q, float* out_scale, void* workspace, size_t workspace_bytes,
+                                       void* stream);
 
 /* ---------------------------------------------------------------------------------------------
  * halo_quant_dual: both quantisations of the output gradient E that levels 0 and 1 need, from one tiling of E.
@@ -191,17 +210,18 @@ halo_status halo_mfma_i8_probe(const int8_t* operands, int32_t iters, int32_t* s
  * halo_dequant_unrotate: the tail of both backward products.   (Table "HALO levels": the trailing H^T
  * of  (E_Y)_Q (WH)_Q H^T  and  (E_Y^T)_Q (XH)_Q H^T,  and the leading H^T of level 2.)
  *
- *   T[r,k] = float(acc[r,k]) * row_scale[r];   T <- T (I (x) H_had_block)   (right-hand, if had_block)
+ *   T[r,k] = (float(acc[r,k]) * row_scale[r]) * tensor_scale[0];   T <- T (I (x) H_had_block)   (right-hand, if had_block)
  *   T <- (I (x) H_had_block_left)^T T          (left-hand, if had_block_left);   out = T rounded to out_dt.
  *
- *   acc int32 [rows x cols] ld_acc; row_scale fp32 [rows] or NULL; out bf16/fp32 [rows x cols] ld_out.
+ *   acc int32 [rows x cols] ld_acc; row_scale fp32 [rows] or NULL; tensor_scale: device pointer to ONE fp32 or NULL
+ *   (the saved operand's scale in the one-scale-per-tensor mode); out bf16/fp32 [rows x cols] ld_out.
  *   workspace: halo_dequant_unrotate_workspace_bytes(rows, cols, had_block_left) bytes.
  */
 size_t halo_dequant_unrotate_workspace_bytes(int64_t rows, int64_t cols, int32_t had_block_left);
 
 halo_status halo_dequant_unrotate(const int32_t* acc, int64_t ld_acc, int64_t rows, int64_t cols,
-                                  const float* row_scale, int32_t had_block, int32_t had_block_left,
-                                  void* out, halo_dtype out_dt, int64_t ld_out, void* workspace,
+                                  const float* row_scale, const float* tensor_scale, int32_t had_block,
+                                  int32_t had_block_left, void* out, halo_dtype out_dt, int64_t ld_out, void* workspace,
                                   size_t workspace_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------------------------
@@ -215,6 +235,12 @@ halo_status halo_dequant_unrotate(const int32_t* acc, int64_t ld_acc, int64_t ro
  *   had_block_m    right-hand block over m; 0 = largest power of two dividing m, capped at 4096.
  *   had_block_b    left-hand block over b (level 2 only); 0 = largest power of two dividing b.
  *   out_dt         type of Y, E_X and G.
+ *   scale_mode     HALO_SCALE_PER_ROW: one scale per row of every GEMM operand; the saved scale vectors are folded
+ *                  into E before E is quantised for the backward products.  HALO_SCALE_PER_TENSOR: the paper's
+ *                  quantiser, one scale per tensor; s_x / s_w hold that scale in every entry; E is quantised as it is
+ *                  (left-rotated at level 2) and the two scales multiply the accumulators afterwards:
+ *                  E_X = ((acc * s_e) * s_w) ...,  G = ((acc * s_g) * s_x) ...   Needs the workspace in the forward
+ *                  pass too.
  */
 typedef struct halo_linear_desc {
     int64_t b, m, n;
@@ -222,8 +248,10 @@ typedef struct halo_linear_desc {
     int32_t had_block_m;
     int32_t had_block_b;
     int32_t out_dt;         /* halo_dtype */
+    int32_t scale_mode;     /* halo_scale_mode */
 } halo_linear_desc;
 
+/* Bytes of device scratch halo_linear_bwd needs (and halo_linear_fwd in the per-tensor mode). */
 size_t halo_linear_workspace_bytes(const halo_linear_desc* desc);
 
 /* Forward.  X bf16 [b x m] (ld m), W bf16 [n x m] (ld m), Y [b x n] (ld n).

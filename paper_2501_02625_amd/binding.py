@@ -19,12 +19,14 @@ HALO_OK = 0
 HALO_EINVAL, HALO_ESHAPE, HALO_EALIGN, HALO_EWORKSPACE, HALO_EUNSUPPORTED, HALO_EHIP = 1, 2, 3, 4, 5, 6
 HALO_BF16, HALO_F32 = 0, 1
 HALO_QUANT_ROWS, HALO_QUANT_COLS_T = 0, 1
+HALO_SCALE_PER_ROW, HALO_SCALE_PER_TENSOR = 0, 1
 HALO_GEMM_AUTO = -1
 HALO_GEMM_CONFIGS = {"256x256x64": 0, "256x256x128": 1, "256x128x128": 2, "128x128x64": 3, "staged_128x128x64": 4}
 
 EXPORTED_SYMBOLS = (
     "halo_status_string", "halo_version",
     "halo_hadamard_quant_workspace_bytes", "halo_hadamard_quant",
+    "halo_hadamard_quant_tensor_workspace_bytes", "halo_hadamard_quant_tensor",
     "halo_quant_dual_workspace_bytes", "halo_quant_dual",
     "halo_quant_dual_static_max_workspace_bytes", "halo_quant_dual_static",
     "halo_gemm_i8", "halo_gemm_i8_desc", "halo_gemm_i8_pair", "halo_mfma_i8_probe",
@@ -50,7 +52,7 @@ class GemmDesc(ctypes.Structure):
 class LinearDesc(ctypes.Structure):
     _fields_ = [("b", ctypes.c_int64), ("m", ctypes.c_int64), ("n", ctypes.c_int64),
                 ("level", ctypes.c_int32), ("had_block_m", ctypes.c_int32),
-                ("had_block_b", ctypes.c_int32), ("out_dt", ctypes.c_int32)]
+                ("had_block_b", ctypes.c_int32), ("out_dt", ctypes.c_int32), ("scale_mode", ctypes.c_int32)]
 
 
 _lib: Optional[ctypes.CDLL] = None
@@ -77,6 +79,10 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.halo_hadamard_quant_workspace_bytes.argtypes = [i64, i64, c.c_int, i32]
     lib.halo_hadamard_quant.restype = c.c_int
     lib.halo_hadamard_quant.argtypes = [vp, c.c_int, i64, i64, i64, c.c_int, i32, i32, vp, vp, i64, vp, vp, sz, vp]
+    lib.halo_hadamard_quant_tensor_workspace_bytes.restype = sz
+    lib.halo_hadamard_quant_tensor_workspace_bytes.argtypes = [i64, i64, c.c_int, i32]
+    lib.halo_hadamard_quant_tensor.restype = c.c_int
+    lib.halo_hadamard_quant_tensor.argtypes = [vp, c.c_int, i64, i64, i64, c.c_int, i32, i32, vp, i64, vp, vp, sz, vp]
     lib.halo_quant_dual_workspace_bytes.restype = sz
     lib.halo_quant_dual_workspace_bytes.argtypes = [i64, i64]
     lib.halo_quant_dual.restype = c.c_int
@@ -96,7 +102,7 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.halo_dequant_unrotate_workspace_bytes.restype = sz
     lib.halo_dequant_unrotate_workspace_bytes.argtypes = [i64, i64, i32]
     lib.halo_dequant_unrotate.restype = c.c_int
-    lib.halo_dequant_unrotate.argtypes = [vp, i64, i64, i64, vp, i32, i32, vp, c.c_int, i64, vp, sz, vp]
+    lib.halo_dequant_unrotate.argtypes = [vp, i64, i64, i64, vp, vp, i32, i32, vp, c.c_int, i64, vp, sz, vp]
     lib.halo_linear_workspace_bytes.restype = sz
     lib.halo_linear_workspace_bytes.argtypes = [c.POINTER(LinearDesc)]
     lib.halo_linear_fwd.restype = c.c_int
@@ -172,6 +178,30 @@ def halo_hadamard_quant(x: torch.Tensor, *, axis: int = HALO_QUANT_ROWS, had_blo
                                  out_q.stride(0) if out_q.numel() else qshape[1], _ptr(out_scale), _ptr(workspace),
                                  workspace.numel() if workspace is not None else 0, _stream())
     _check(st, "halo_hadamard_quant")
+    return out_q, out_scale
+
+
+def halo_hadamard_quant_tensor(x: torch.Tensor, *, axis: int = HALO_QUANT_ROWS, had_block: int = 0,
+                               had_block_left: int = 0, out_q: Optional[torch.Tensor] = None,
+                               out_scale: Optional[torch.Tensor] = None,
+                               workspace: Optional[torch.Tensor] = None) -> Tuple[torch.Tensor, torch.Tensor]:
+    """rotate -> absmax of the whole tensor -> INT8.  Returns (codes int8, scales fp32: the one scale in every entry)."""
+    lib = load_library()
+    _need_cuda(x, out_q, out_scale, workspace)
+    assert x.dim() == 2 and x.stride(1) == 1
+    rows, cols = x.shape
+    qshape, nscale = ((rows, cols), rows) if axis == HALO_QUANT_ROWS else ((cols, rows), cols)
+    if out_q is None:
+        out_q = _empty_padded(qshape[0], qshape[1], torch.int8, x.device)
+    if out_scale is None:
+        out_scale = torch.empty((nscale,), dtype=torch.float32, device=x.device)
+    need = lib.halo_hadamard_quant_tensor_workspace_bytes(rows, cols, axis, had_block_left)
+    if workspace is None:
+        workspace = torch.empty((max(need, 16),), dtype=torch.uint8, device=x.device)
+    st = lib.halo_hadamard_quant_tensor(_ptr(x), _dt(x.dtype), rows, cols, x.stride(0) if rows else cols, axis, had_block,
+                                        had_block_left, _ptr(out_q), out_q.stride(0) if out_q.numel() else qshape[1],
+                                        _ptr(out_scale), _ptr(workspace), workspace.numel(), _stream())
+    _check(st, "halo_hadamard_quant_tensor")
     return out_q, out_scale
 
 
@@ -277,9 +307,10 @@ def halo_mfma_i8_probe(operands: torch.Tensor, iters: int, sink: Optional[torch.
 
 def halo_dequant_unrotate(acc: torch.Tensor, row_scale: Optional[torch.Tensor], *, had_block: int = 0,
                           had_block_left: int = 0, out_dtype: torch.dtype = torch.float32,
-                          out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+                          out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+                          tensor_scale: Optional[torch.Tensor] = None) -> torch.Tensor:
     lib = load_library()
-    _need_cuda(acc, row_scale, out, workspace)
+    _need_cuda(acc, row_scale, out, workspace, tensor_scale)
     assert acc.dtype == torch.int32 and acc.dim() == 2
     rows, cols = acc.shape
     if out is None:
@@ -287,8 +318,8 @@ def halo_dequant_unrotate(acc: torch.Tensor, row_scale: Optional[torch.Tensor], 
     need = lib.halo_dequant_unrotate_workspace_bytes(rows, cols, had_block_left)
     if workspace is None and need:
         workspace = torch.empty((need,), dtype=torch.uint8, device=acc.device)
-    st = lib.halo_dequant_unrotate(_ptr(acc), acc.stride(0) if rows else cols, rows, cols, _ptr(row_scale), had_block,
-                                   had_block_left, _ptr(out), _dt(out.dtype), out.stride(0) if rows else cols,
+    st = lib.halo_dequant_unrotate(_ptr(acc), acc.stride(0) if rows else cols, rows, cols, _ptr(row_scale),
+                                   _ptr(tensor_scale), had_block, had_block_left, _ptr(out), _dt(out.dtype), out.stride(0) if rows else cols,
                                    _ptr(workspace), workspace.numel() if workspace is not None else 0, _stream())
     _check(st, "halo_dequant_unrotate")
     return out
@@ -304,8 +335,8 @@ class LinearState:
 
 
 def make_desc(b: int, m: int, n: int, level: int, out_dtype: torch.dtype = torch.bfloat16,
-              had_block_m: int = 0, had_block_b: int = 0) -> LinearDesc:
-    return LinearDesc(b, m, n, level, had_block_m, had_block_b, _dt(out_dtype))
+              had_block_m: int = 0, had_block_b: int = 0, scale_mode: int = HALO_SCALE_PER_ROW) -> LinearDesc:
+    return LinearDesc(b, m, n, level, had_block_m, had_block_b, _dt(out_dtype), scale_mode)
 
 
 def halo_linear_workspace_bytes(desc: LinearDesc) -> int:
@@ -313,7 +344,8 @@ def halo_linear_workspace_bytes(desc: LinearDesc) -> int:
 
 
 def halo_linear_fwd(desc: LinearDesc, X: Optional[torch.Tensor], W: Optional[torch.Tensor], *,
-                    state: Optional[LinearState] = None, Y: Optional[torch.Tensor] = None):
+                    state: Optional[LinearState] = None, Y: Optional[torch.Tensor] = None,
+                    workspace: Optional[torch.Tensor] = None):
     """Forward product; returns (Y, LinearState).  Pass X=None / W=None with a `state` that already holds
     the corresponding codes to reuse them."""
     lib = load_library()
@@ -329,8 +361,11 @@ def halo_linear_fwd(desc: LinearDesc, X: Optional[torch.Tensor], W: Optional[tor
     _need_cuda(X, W, Y, state.Xq, state.Wq)
     for t in (X, W):
         assert t is None or (t.dtype == torch.bfloat16 and t.is_contiguous())
+    if workspace is None and desc.scale_mode == HALO_SCALE_PER_TENSOR:
+        workspace = torch.empty((max(halo_linear_workspace_bytes(desc), 16),), dtype=torch.uint8, device=dev)
     st = lib.halo_linear_fwd(ctypes.byref(desc), _ptr(X), _ptr(W), _ptr(Y), _ptr(state.Xq), _ptr(state.s_x),
-                             _ptr(state.Wq), _ptr(state.s_w), None, 0, _stream())
+                             _ptr(state.Wq), _ptr(state.s_w), _ptr(workspace),
+                             workspace.numel() if workspace is not None else 0, _stream())
     _check(st, "halo_linear_fwd")
     return Y, state
 

@@ -159,6 +159,27 @@ __global__ void __launch_bounds__(256) fill_u32_kernel(uint32_t* p, int64_t n, u
     if (i < n) p[i] = value;
 }
 
+__global__ void __launch_bounds__(256) fill_from_scalar_kernel(uint32_t* p, int64_t n, const float* value) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n) p[i] = __float_as_uint(*value);
+}
+
+// out[0] = max over in[0..n-1]: one workgroup (the vectors reduced here are per-row maxima, a few thousand entries).
+__global__ void __launch_bounds__(1024) reduce_max_kernel(const float* in, int64_t n, float* out) {
+    __shared__ float s_part[16];
+    float m = 0.0f;
+    for (int64_t i = threadIdx.x; i < n; i += 1024) m = fmaxf(m, in[i]);
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
+    if ((threadIdx.x & 63) == 0) s_part[threadIdx.x >> 6] = m;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float t = s_part[0];
+        for (int i = 1; i < 16; ++i) t = fmaxf(t, s_part[i]);
+        out[0] = t;
+    }
+}
+
 constexpr int kAmaxRows = 64;   // rows per workgroup in the absmax pass
 __global__ void __launch_bounds__(256)
 col_amax_kernel(const uint16_t* in, int64_t ld_in, int64_t rows, int64_t cols, const float* fold, uint32_t* amax_bits) {
@@ -290,7 +311,7 @@ col_quant_t_kernel(const uint16_t* in, int64_t ld_in, int64_t rows, int64_t cols
 // Both quantisations of E that the backward pass needs, from one tiling of E:
 //   rows:  Eq [b x n]  = Q_row( E[i,j] * fold_c[j] )   (the saved weight scales folded in; feeds E_X = E W)
 //   cols:  EqT [n x b] = Q_row( (E[i,j] * fold_r[i])^T ) (the saved activation scales folded in; feeds G = E^T X)
-// Pass 1 accumulates both absmax vectors with integer atomic max on the bit patterns (exact, order-free); pass 2
+// Pass 1 writes the partial maxima of both absmax vectors per tile (no atomics); pass 2 reduces the partials it needs,
 // re-reads E (cache-hot), emits the row-wise codes directly and the column-wise codes through an LDS transpose.
 constexpr int kAR = 32, kAC = 256;                               // absmax pass: tile rows, tile columns
 constexpr int kDR = 128, kDC = 128, kDPitch = kDR / 4 + 1;     // quantising pass: tile rows, columns, LDS dwords per column
@@ -572,6 +593,25 @@ hipError_t launch_dual_quant_static(DualQuantArgs a, hipStream_t s) {
     if (e != hipSuccess) return e;
     a.amax_ws = reinterpret_cast<float*>(p);     // every entry pass 2 reads is written by pass 1 first: nothing to clear
     return launch_dual_quant(a, s);
+}
+
+hipError_t launch_reduce_max(const float* in, int64_t n, float* out, hipStream_t s) {
+    if (n <= 0) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(reduce_max_kernel, dim3(1), dim3(1024), 0, s, in, n, out);
+    return hipGetLastError();
+}
+
+hipError_t launch_col_quant_t_given(const ColQuantArgs& a, const float* given_amax, hipStream_t s) {
+    if (a.rows == 0 || a.cols == 0) return hipSuccess;
+    uint32_t* amax_bits = reinterpret_cast<uint32_t*>(a.amax_ws);
+    hipLaunchKernelGGL(fill_from_scalar_kernel, dim3((unsigned)((a.cols + 255) / 256)), dim3(256), 0, s, amax_bits, a.cols,
+                       given_amax);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const dim3 g2((unsigned)((a.cols + kTJ - 1) / kTJ), (unsigned)((a.rows + kTI - 1) / kTI));
+    hipLaunchKernelGGL(col_quant_t_kernel, g2, dim3(256), 0, s, reinterpret_cast<const uint16_t*>(a.in), a.ld_in,
+                       a.rows, a.cols, a.fold, amax_bits, a.out_q, a.ld_q, a.out_scale);
+    return hipGetLastError();
 }
 
 hipError_t launch_col_quant_t(const ColQuantArgs& a, hipStream_t s) {

@@ -6,10 +6,6 @@
 
 using namespace halo;
 
-#ifndef HALO_BATCH_ROWS
-#define HALO_BATCH_ROWS 1     // one row-kernel launch for X and W (forward) and for both accumulators (backward, level 1)
-#endif
-
 namespace {
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -31,7 +27,7 @@ constexpr int64_t kMaxLeftBlock = 65536;
 constexpr int64_t kMaxDim = int64_t(1) << 22;   // rows / columns of any matrix argument
 
 struct BwdWorkspace {
-    size_t eq, s_e, eqt, s_g, amax, acc, acc_g, f32, total;
+    size_t eq, s_e, eqt, s_g, amax, acc, acc_g, f32, tq, total;
 };
 
 inline bool acc_fits_int32(int64_t k) { return 127ll * 127ll * k < (1ll << 31); }
@@ -47,6 +43,7 @@ halo_status resolve_desc(const halo_linear_desc* d, int32_t* hm, int32_t* hb) {
     if (d->b < 0 || d->m < 0 || d->n < 0) return HALO_EINVAL;
     if (d->level < 0 || d->level > 2) return HALO_EINVAL;
     if (d->out_dt != HALO_BF16 && d->out_dt != HALO_F32) return HALO_EINVAL;
+    if (d->scale_mode != HALO_SCALE_PER_ROW && d->scale_mode != HALO_SCALE_PER_TENSOR) return HALO_EINVAL;
     if (d->b > kMaxDim || d->m > kMaxDim || d->n > kMaxDim) return HALO_EUNSUPPORTED;
     if (d->b % 16 || d->m % 16 || d->n % 16) return HALO_ESHAPE;
     if (d->m > kMaxRowCols || d->n > kMaxRowCols) return HALO_EUNSUPPORTED;
@@ -81,6 +78,11 @@ BwdWorkspace bwd_layout(const halo_linear_desc* d) {
     w.acc_g = off; off += round256(n * m * 4);      // accumulators of the G product
     w.f32 = off;
     if (d->level >= 2) off += round256(b * (m > n ? m : n) * 4);
+    w.tq = off;                                     // scratch of the one-scale-per-tensor quantiser (without its left part)
+    if (d->scale_mode == HALO_SCALE_PER_TENSOR) {
+        const size_t longest = b > n ? b : n;
+        off += round256((longest + 64) * 4) + round256(n * 4);
+    }
     w.total = off;
     return w;
 }
@@ -102,7 +104,7 @@ const char* halo_status_string(halo_status s) {
     return "unknown status";
 }
 
-int halo_version(void) { return 1; }
+int halo_version(void) { return 2; }
 
 // ------------------------------------------------------------------------------------------------
 size_t halo_hadamard_quant_workspace_bytes(int64_t rows, int64_t cols, halo_axis axis, int32_t had_block_left) {
@@ -159,6 +161,75 @@ halo_status halo_hadamard_quant(const void* in, halo_dtype in_dt, int64_t rows, 
     if (e != hipSuccess) return HALO_EHIP;
     r.in = tmp; r.ld_in = cols;
     return from_hip(launch_row_transform(r, IN_F32, OUT_Q8, s));
+}
+
+// ------------------------------------------------------------------------------------------------
+// Workspace of the tensor-wide quantiser: [left-rotation scratch fp32 rows x cols] [row maxima: rows floats]
+// [tensor maximum: 64 floats] [column quantiser: cols floats].
+size_t halo_hadamard_quant_tensor_workspace_bytes(int64_t rows, int64_t cols, halo_axis axis, int32_t had_block_left) {
+    if (rows <= 0 || cols <= 0) return 0;
+    size_t need = round256(((size_t)rows + 64) * 4);
+    if (axis == HALO_QUANT_COLS_T) need += round256((size_t)cols * 4);
+    if (had_block_left > 0) need += round256((size_t)rows * (size_t)cols * 4);
+    return need;
+}
+
+halo_status halo_hadamard_quant_tensor(const void* in, halo_dtype in_dt, int64_t rows, int64_t cols, int64_t ld_in,
+                                       halo_axis axis, int32_t had_block, int32_t had_block_left, int8_t* out_q,
+                                       int64_t ld_q, float* out_scale, void* workspace, size_t workspace_bytes,
+                                       void* stream) {
+    if (rows < 0 || cols < 0) return HALO_EINVAL;
+    if (in_dt != HALO_BF16 && in_dt != HALO_F32) return HALO_EINVAL;
+    if (axis != HALO_QUANT_ROWS && axis != HALO_QUANT_COLS_T) return HALO_EINVAL;
+    if (rows == 0 || cols == 0) return HALO_OK;
+    if (!in || !out_q || !out_scale) return HALO_EINVAL;
+    if (rows > kMaxDim || cols > kMaxDim) return HALO_EUNSUPPORTED;
+    if (cols > kMaxRowCols) return HALO_EUNSUPPORTED;
+    const int64_t esz = in_dt == HALO_BF16 ? 2 : 4;
+    if (ld_in < cols) return HALO_ESHAPE;
+    if (ld_q < (axis == HALO_QUANT_ROWS ? cols : rows)) return HALO_ESHAPE;
+    if (!aligned16(in) || !aligned16(out_q) || (ld_in * esz) % 16 || ld_q % 16) return HALO_EALIGN;
+    halo_status st = check_block(had_block, cols, kMaxRightBlock);
+    if (st != HALO_OK) return st;
+    st = check_block(had_block_left, rows, kMaxLeftBlock);
+    if (st != HALO_OK) return st;
+    if (axis == HALO_QUANT_COLS_T && (had_block || had_block_left || in_dt != HALO_BF16)) return HALO_EUNSUPPORTED;
+    const size_t need = halo_hadamard_quant_tensor_workspace_bytes(rows, cols, axis, had_block_left);
+    if (!workspace || workspace_bytes < need) return HALO_EWORKSPACE;
+    if (!aligned16(workspace)) return HALO_EALIGN;
+    if (had_block_left > 0 && (cols * 4) % 16) return HALO_EALIGN;
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    unsigned char* ws = reinterpret_cast<unsigned char*>(workspace);
+    float* row_max = reinterpret_cast<float*>(ws);
+    float* tensor_max = row_max + rows;                        // 64 floats reserved, one used
+    unsigned char* next = ws + round256(((size_t)rows + 64) * 4);
+    float* col_ws = reinterpret_cast<float*>(next);
+    if (axis == HALO_QUANT_COLS_T) next += round256((size_t)cols * 4);
+    float* tmp = reinterpret_cast<float*>(next);
+
+    // what the row kernel reads: the input itself, or its left-rotated fp32 copy
+    const void* src = in;
+    int64_t ld_src = ld_in;
+    InKind src_kind = in_dt == HALO_BF16 ? IN_BF16 : IN_F32;
+    if (had_block_left > 0) {
+        ColFwhtArgs c{in, src_kind, ld_in, tmp, OUT_F32, cols, tmp, cols, rows, cols, ilog2_exact(had_block_left)};
+        if (launch_col_fwht(c, s) != hipSuccess) return HALO_EHIP;
+        src = tmp; ld_src = cols; src_kind = IN_F32;
+    }
+    // phase 1: rotate, absmax of every row; then the maximum of those
+    RowArgs r{};
+    r.in = src; r.ld_in = ld_src; r.rows = rows; r.cols = cols;
+    r.log_block = had_block ? ilog2_exact(had_block) : 0;
+    r.out = out_q; r.ld_out = ld_q; r.out_scale = row_max; r.amax_only = 1;
+    if (launch_row_transform(r, src_kind, OUT_Q8, s) != hipSuccess) return HALO_EHIP;
+    if (launch_reduce_max(row_max, rows, tensor_max, s) != hipSuccess) return HALO_EHIP;
+    // phase 2: rotate again and quantise with the tensor's absmax
+    if (axis == HALO_QUANT_COLS_T) {
+        ColQuantArgs a{in, ld_in, rows, cols, nullptr, out_q, ld_q, out_scale, col_ws};
+        return from_hip(launch_col_quant_t_given(a, tensor_max, s));
+    }
+    r.amax_only = 0; r.given_amax = tensor_max; r.out_scale = out_scale;
+    return from_hip(launch_row_transform(r, src_kind, OUT_Q8, s));
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -280,9 +351,9 @@ size_t halo_dequant_unrotate_workspace_bytes(int64_t rows, int64_t cols, int32_t
 }
 
 halo_status halo_dequant_unrotate(const int32_t* acc, int64_t ld_acc, int64_t rows, int64_t cols,
-                                  const float* row_scale, int32_t had_block, int32_t had_block_left, void* out,
-                                  halo_dtype out_dt, int64_t ld_out, void* workspace, size_t workspace_bytes,
-                                  void* stream) {
+                                  const float* row_scale, const float* tensor_scale, int32_t had_block,
+                                  int32_t had_block_left, void* out, halo_dtype out_dt, int64_t ld_out, void* workspace,
+                                  size_t workspace_bytes, void* stream) {
     if (rows < 0 || cols < 0) return HALO_EINVAL;
     if (out_dt != HALO_BF16 && out_dt != HALO_F32) return HALO_EINVAL;
     if (rows == 0 || cols == 0) return HALO_OK;
@@ -301,7 +372,7 @@ halo_status halo_dequant_unrotate(const int32_t* acc, int64_t ld_acc, int64_t ro
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
 
     RowArgs r{};
-    r.in = acc; r.ld_in = ld_acc; r.rows = rows; r.cols = cols; r.pre_scale = row_scale;
+    r.in = acc; r.ld_in = ld_acc; r.rows = rows; r.cols = cols; r.pre_scale = row_scale; r.post_scale = tensor_scale;
     r.log_block = had_block ? ilog2_exact(had_block) : 0;
     if (had_block_left == 0) {
         r.out = out; r.ld_out = ld_out;
@@ -326,7 +397,6 @@ size_t halo_linear_workspace_bytes(const halo_linear_desc* desc) {
 halo_status halo_linear_fwd(const halo_linear_desc* desc, const void* X, const void* W, void* Y, int8_t* Xq,
                             float* s_x, int8_t* Wq, float* s_w, void* workspace, size_t workspace_bytes,
                             void* stream) {
-    (void)workspace; (void)workspace_bytes;
     int32_t hm, hb;
     halo_status st = resolve_desc(desc, &hm, &hb);
     if (st != HALO_OK) return st;
@@ -336,7 +406,25 @@ halo_status halo_linear_fwd(const halo_linear_desc* desc, const void* X, const v
     if ((X && !aligned16(X)) || (W && !aligned16(W)) || !aligned16(Y) || !aligned16(Xq) || !aligned16(Wq))
         return HALO_EALIGN;
     const halo_dtype odt = (halo_dtype)desc->out_dt;
-    if (HALO_BATCH_ROWS && X && W && m <= kMaxRowCols) {
+    const bool tensor = desc->scale_mode == HALO_SCALE_PER_TENSOR;
+    if (tensor && (X || W)) {
+        // one scale per tensor (the paper's quantiser): two passes per operand, scratch from the workspace
+        const BwdWorkspace L = bwd_layout(desc);
+        if (!workspace || workspace_bytes < L.total) return HALO_EWORKSPACE;
+        if (!aligned16(workspace)) return HALO_EALIGN;
+        unsigned char* tq = reinterpret_cast<unsigned char*>(workspace) + L.tq;
+        const size_t tq_bytes = L.total - L.tq;
+        if (X) {
+            st = halo_hadamard_quant_tensor(X, HALO_BF16, b, m, m, HALO_QUANT_ROWS, hm, 0, Xq, m, s_x, tq, tq_bytes, stream);
+            if (st != HALO_OK) return st;
+        }
+        if (W) {
+            st = halo_hadamard_quant_tensor(W, HALO_BF16, n, m, m, HALO_QUANT_ROWS, hm, 0, Wq, m, s_w, tq, tq_bytes, stream);
+            if (st != HALO_OK) return st;
+        }
+        return halo_gemm_i8(Xq, m, Wq, m, 1, b, n, m, s_x, s_w, Y, odt, n, nullptr, 0, stream);
+    }
+    if (X && W && !tensor) {
         // X and W get the same treatment: one launch rotates and quantises both
         RowArgs r{};
         r.in = X; r.ld_in = m; r.rows = b; r.cols = m; r.out = Xq; r.ld_out = m; r.out_scale = s_x;
@@ -384,6 +472,41 @@ halo_status halo_linear_bwd(const halo_linear_desc* desc, const void* E, const i
 
     hipStream_t hs = reinterpret_cast<hipStream_t>(stream);
     const bool both = EX && G;
+    const bool tensor = desc->scale_mode == HALO_SCALE_PER_TENSOR;
+
+    if (tensor) {
+        // The paper's scalar scales factor out of the integer sums: E is quantised as it is (left-rotated at level
+        // 2), and E's scale and the saved tensor's scale multiply the accumulators afterwards, in that order.
+        unsigned char* tq = ws + L.tq;
+        const size_t tq_bytes = L.total - L.tq;
+        // The left-rotated copy of E is made here, in the layer's fp32 scratch, and handed to the quantiser as fp32
+        // input (the un-rotation reuses that scratch afterwards).
+        if (EX) {
+            const void* src = E;
+            halo_dtype src_dt = HALO_BF16;
+            if (level >= 2) {
+                ColFwhtArgs c{E, IN_BF16, n, f32, OUT_F32, n, f32, n, b, n, ilog2_exact(hb)};
+                if (launch_col_fwht(c, hs) != hipSuccess) return HALO_EHIP;
+                src = f32; src_dt = HALO_F32;
+            }
+            st = halo_hadamard_quant_tensor(src, src_dt, b, n, n, HALO_QUANT_ROWS, 0, 0, Eq, n, s_e, tq, tq_bytes, stream);
+            if (st != HALO_OK) return st;
+            GemmArgs gx{Eq, n, Wq, m, 0, b, m, n, nullptr, nullptr, nullptr, 0, m, acc, m, HALO_GEMM_AUTO};
+            if (launch_gemm_i8(gx, hs) != hipSuccess) return HALO_EHIP;
+            st = halo_dequant_unrotate(acc, m, b, m, s_e, s_w, level >= 1 ? hm : 0, level >= 2 ? hb : 0, EX, odt, m, f32,
+                                       level >= 2 ? round256((size_t)b * m * 4) : 0, stream);
+            if (st != HALO_OK) return st;
+        }
+        if (G) {
+            st = halo_hadamard_quant_tensor(E, HALO_BF16, b, n, n, HALO_QUANT_COLS_T, 0, 0, EqT, b, s_g, tq, tq_bytes, stream);
+            if (st != HALO_OK) return st;
+            GemmArgs gg{EqT, b, Xq, m, 0, n, m, b, nullptr, nullptr, nullptr, 0, m, acc_g, m, HALO_GEMM_AUTO};
+            if (launch_gemm_i8(gg, hs) != hipSuccess) return HALO_EHIP;
+            st = halo_dequant_unrotate(acc_g, m, n, m, s_g, s_x, level >= 1 ? hm : 0, 0, G, odt, m, nullptr, 0, stream);
+            if (st != HALO_OK) return st;
+        }
+        return HALO_OK;
+    }
 
     // ---- quantise E: per row for the E product (left-rotated first at level 2), per column (transposed) for G.
     // Levels 0 and 1 want both from the same E: one tiling of E does both.
@@ -417,7 +540,7 @@ halo_status halo_linear_bwd(const halo_linear_desc* desc, const void* E, const i
     if (level == 0) return HALO_OK;
 
     // ---- dequantise and un-rotate
-    if (HALO_BATCH_ROWS && both && level == 1) {
+    if (both && level == 1 && !tensor) {
         RowArgs r{};
         r.in = acc; r.ld_in = m; r.rows = b; r.cols = m; r.pre_scale = s_e; r.out = EX; r.ld_out = m;
         r.log_block = hm ? ilog2_exact(hm) : 0;
@@ -426,12 +549,12 @@ halo_status halo_linear_bwd(const halo_linear_desc* desc, const void* E, const i
         return HALO_OK;
     }
     if (EX) {
-        st = halo_dequant_unrotate(acc, m, b, m, s_e, hm, level >= 2 ? hb : 0, EX, odt, m, f32,
+        st = halo_dequant_unrotate(acc, m, b, m, s_e, nullptr, hm, level >= 2 ? hb : 0, EX, odt, m, f32,
                                    level >= 2 ? round256((size_t)b * m * 4) : 0, stream);
         if (st != HALO_OK) return st;
     }
     if (G) {
-        st = halo_dequant_unrotate(acc_g, m, n, m, s_g, hm, 0, G, odt, m, nullptr, 0, stream);
+        st = halo_dequant_unrotate(acc_g, m, n, m, s_g, nullptr, hm, 0, G, odt, m, nullptr, 0, stream);
         if (st != HALO_OK) return st;
     }
     return HALO_OK;

@@ -22,6 +22,12 @@ struct RowArgs {
     int64_t ld_out;
     float* out_scale;        // OUT_Q8 only
     int log_block;           // log2 of the Hadamard block, 0 = no rotation
+    // One scale per tensor (OUT_Q8 only): amax_only writes each row's absmax to out_scale and no codes; given_amax
+    // (device scalar) replaces the row's own absmax.  post_scale (IN_I32 only, device scalar) is multiplied in after
+    // pre_scale.  All three apply to both matrices of a batched launch.
+    int amax_only;
+    const float* given_amax;
+    const float* post_scale;
     // Optional second matrix handled by the same launch (same cols, leading dimensions, fold and block; its own
     // row count and buffers): rows2 == 0 means none.  Saves one launch ramp/tail when two independent tensors get
     // the same treatment (X and W in the forward pass, the two accumulators of the backward pass).
@@ -64,6 +70,10 @@ struct ColQuantArgs {
     float* amax_ws;          // [cols] scratch: column absmax accumulated as bit patterns
 };
 hipError_t launch_col_quant_t(const ColQuantArgs& a, hipStream_t s);
+// The same with one given absmax (device scalar) for every column instead of the columns' own: the tensor-wide scale.
+hipError_t launch_col_quant_t_given(const ColQuantArgs& a, const float* given_amax, hipStream_t s);
+// out[0] = max(in[0..n-1]) (n >= 1, non-negative values).
+hipError_t launch_reduce_max(const float* in, int64_t n, float* out, hipStream_t s);
 
 // ---- both quantisations of E for the backward pass from one tiling (rows for E_X, transposed columns for G) ----
 struct DualQuantArgs {

@@ -24,12 +24,6 @@
 namespace halo {
 namespace {
 
-// Build-time switch (both settings give identical bits): fold a power-of-two 1/sqrt(d) into the quantiser
-// scale instead of multiplying every element by it.
-#ifndef HALO_ROW_FOLD_C
-#define HALO_ROW_FOLD_C 0
-#endif
-
 constexpr float kRoundMagic = 12582912.0f;  // 1.5 * 2^23: adding it rounds |x| < 2^22 to an integer, ties to even
 
 template <int J>
@@ -158,7 +152,7 @@ struct RowCtx {
 // FAST: the row exists and the whole segment lies inside it, so nothing is bounds-checked.
 template <int LOGSEG, int IN, int OUT, bool FAST, int LB, int XS>
 __device__ __forceinline__ float row_phase1(const RowArgs& a, const RowCtx& x, float c_norm,
-                                            float (&v)[1 << (LOGSEG - 6)], float& sign_l, bool& fold_c) {
+                                            float (&v)[1 << (LOGSEG - 6)]) {
     constexpr int LOGE = (IN == IN_BF16) ? 3 : 2;
     constexpr int EPL = 1 << LOGE;
     constexpr int VPL = 1 << (LOGSEG - 6);
@@ -209,10 +203,16 @@ __device__ __forceinline__ float row_phase1(const RowArgs& a, const RowCtx& x, f
         }
     }
 
+    if constexpr (IN == IN_I32) {
+        if (a.post_scale) {          // one more (tensor-wide) scale, applied after the per-row one
+            const float post = *a.post_scale;
+#pragma unroll
+            for (int r = 0; r < VPL; ++r) v[r] *= post;
+        }
+    }
+
     // ---- rotate (LB >= 0: block size known at compile time, so the stage sequence is straight-line code)
     const int log_block = LB >= 0 ? LB : a.log_block;
-    sign_l = 1.0f;       // pending per-lane sign of the register contents
-    fold_c = false;      // pending multiplication by c_norm
     if (log_block > 0) {
         FwhtStages<VPL, LOGE, 0, LOGSEG>::run(v, log_block, x.lane, x.bperm_addr);
         if constexpr (XS > 0) {
@@ -234,20 +234,14 @@ __device__ __forceinline__ float row_phase1(const RowArgs& a, const RowCtx& x, f
                 }
             }
         }
-        // lanes whose (lane & mask) has odd parity hold negated values
+        // lanes whose (lane & mask) has odd parity hold negated values: the sign rides on the 1/sqrt(d) multiply
         int nlane_stages = log_block - LOGE;
         nlane_stages = nlane_stages < 0 ? 0 : (nlane_stages > 6 ? 6 : nlane_stages);
         const int mask = (1 << nlane_stages) - 1;
-        sign_l = (__builtin_popcount(x.lane & mask) & 1) ? -1.0f : 1.0f;
-        // 1/sqrt(d): one multiply per element, except that a power of two is folded into the quantiser scale
-        // (the same bits as long as nothing underflows, which the absmax test in the caller ensures).
-        fold_c = HALO_ROW_FOLD_C && OUT == OUT_Q8 && !a.fold && (log_block % 2 == 0);
-        if (!fold_c) {
-            const float c_l = sign_l * c_norm;
+        const float sign_l = (__builtin_popcount(x.lane & mask) & 1) ? -1.0f : 1.0f;
+        const float c_l = sign_l * c_norm;
 #pragma unroll
-            for (int r = 0; r < VPL; ++r) v[r] *= c_l;
-            sign_l = 1.0f;
-        }
+        for (int r = 0; r < VPL; ++r) v[r] *= c_l;
     }
 
     // ---- fold
@@ -390,10 +384,8 @@ row_transform_kernel(RowArgs a, int segs, int rows_per_wg, float c_norm, unsigne
     const bool fast = x.row_ok && ((int64_t)(seg + 1) * SEG <= a.cols);   // uniform over the wavefront
 
     float v[VPL];
-    float sign_l;
-    bool fold_c;
-    float amax = fast ? row_phase1<LOGSEG, IN, OUT, true, LB, XS>(a, x, c_norm, v, sign_l, fold_c)
-                      : row_phase1<LOGSEG, IN, OUT, false, LB, XS>(a, x, c_norm, v, sign_l, fold_c);
+    float amax = fast ? row_phase1<LOGSEG, IN, OUT, true, LB, XS>(a, x, c_norm, v)
+                      : row_phase1<LOGSEG, IN, OUT, false, LB, XS>(a, x, c_norm, v);
 
     float inv_l = 0.0f;
     if constexpr (OUT == OUT_Q8) {
@@ -405,27 +397,19 @@ row_transform_kernel(RowArgs a, int segs, int rows_per_wg, float c_norm, unsigne
             for (int i = 1; i < segs; ++i) t = fmaxf(t, s_amax[w0 + i]);
             amax = t;
         }
-        float amax_t = amax;
-        if (fold_c) {
-            amax_t = amax * c_norm;                      // exact: c_norm is a power of two here
-            if (amax_t < 1e-30f && amax > 0.0f) {        // too close to underflow: take the plain path
-#pragma unroll
-                for (int r = 0; r < VPL; ++r) v[r] *= c_norm;
-                fold_c = false;
-            }
+        if (a.amax_only) {
+            // first phase of the one-scale-per-tensor quantiser: the row's absmax, nothing else
+            if (x.row_ok && seg == 0 && x.lane == 0) a.out_scale[x.row] = amax;
+            return;
         }
-        const bool nz = amax_t > 0.0f;
-        const float inv = nz ? 127.0f / amax_t : 0.0f;
-        inv_l = (fold_c ? inv * c_norm : inv) * sign_l;
-        if (x.row_ok && seg == 0 && x.lane == 0) a.out_scale[x.row] = nz ? amax_t / 127.0f : 1.0f;
+        if (a.given_amax) amax = *a.given_amax;          // second phase: the tensor's absmax for every row
+        const bool nz = amax > 0.0f;
+        inv_l = nz ? 127.0f / amax : 0.0f;
+        if (x.row_ok && seg == 0 && x.lane == 0) a.out_scale[x.row] = nz ? amax / 127.0f : 1.0f;
     }
     if (fast) row_phase2<LOGSEG, IN, OUT, true>(a, x, v, inv_l);
     else row_phase2<LOGSEG, IN, OUT, false>(a, x, v, inv_l);
 }
-
-#ifndef HALO_ROW_SPLIT
-#define HALO_ROW_SPLIT 2      // 0: never split a Hadamard block over wavefronts, 1: whenever possible, 2: by size
-#endif
 
 // Hadamard block of 2^(10+XS) elements handled by 2^XS wavefronts of 1024 elements each: four times the
 // wavefronts of the one-wavefront-per-block layout and a quarter of the registers, at the price of XS round trips
@@ -469,12 +453,10 @@ hipError_t launch_by_seg(const RowArgs& a, hipStream_t s) {
     // Split blocks of 2048 / 4096 over 2 / 4 wavefronts (measured): the 32-bit-input un-rotation gains at every size
     // for 4096-blocks (5.7 vs 5.2 TB/s at 32768 rows, 12.7 vs 16.0 us at 2048 rows); the quantiser only when whole
     // rows would leave the 1024 SIMDs with fewer than four wavefronts each.
-    if (HALO_ROW_SPLIT && (a.log_block == 11 || a.log_block == 12) && a.cols % 1024 == 0 && a.cols <= 16384) {
+    if ((a.log_block == 11 || a.log_block == 12) && a.cols % 1024 == 0 && a.cols <= 16384) {
         const int64_t wavefronts_unsplit = (a.rows + a.rows2) * (a.cols >> a.log_block);
         const bool want = IN == IN_I32 ? a.log_block == 12 : wavefronts_unsplit < 4096;
-        if (HALO_ROW_SPLIT == 1 || want) {
-            return a.log_block == 11 ? launch_split<IN, OUT, 1>(a, s) : launch_split<IN, OUT, 2>(a, s);
-        }
+        if (want) return a.log_block == 11 ? launch_split<IN, OUT, 1>(a, s) : launch_split<IN, OUT, 2>(a, s);
     }
     // Segment = max(Hadamard block, 512), grown until the row fits the workgroup (16 waves, 8 from 2048 up).
     int logseg = a.log_block < 9 ? 9 : a.log_block;

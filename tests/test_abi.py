@@ -154,11 +154,32 @@ def test_linear_desc_errors_and_workspace(lib):
 def test_dequant_unrotate_argument_errors(lib):
     f = lib.halo_dequant_unrotate
     A, O = _p(0x1000), _p(0x2000)
-    assert f(None, 64, 16, 64, None, 64, 0, O, 1, 64, None, 0, None) == binding.HALO_EINVAL
-    assert f(A, 64, 16, 64, None, 48, 0, O, 1, 64, None, 0, None) == binding.HALO_ESHAPE
-    assert f(A, 64, 16, 64, None, 64, 16, O, 1, 64, None, 0, None) == binding.HALO_EWORKSPACE
-    assert f(A, 32, 16, 64, None, 64, 0, O, 1, 64, None, 0, None) == binding.HALO_ESHAPE
-    assert f(A, 64, 16, 64, None, 64, 0, O, 0, 68, None, 0, None) == binding.HALO_EALIGN
+    assert f(None, 64, 16, 64, None, None, 64, 0, O, 1, 64, None, 0, None) == binding.HALO_EINVAL
+    assert f(A, 64, 16, 64, None, None, 48, 0, O, 1, 64, None, 0, None) == binding.HALO_ESHAPE
+    assert f(A, 64, 16, 64, None, None, 64, 16, O, 1, 64, None, 0, None) == binding.HALO_EWORKSPACE
+    assert f(A, 32, 16, 64, None, None, 64, 0, O, 1, 64, None, 0, None) == binding.HALO_ESHAPE
+    assert f(A, 64, 16, 64, None, None, 64, 0, O, 0, 68, None, 0, None) == binding.HALO_EALIGN
+
+
+def test_hadamard_quant_tensor_argument_errors(lib):
+    f = lib.halo_hadamard_quant_tensor
+    A, Q, S, W = _p(0x1000), _p(0x2000), _p(0x3000), _p(0x4000)
+    need = lib.halo_hadamard_quant_tensor_workspace_bytes(64, 512, 0, 0)
+    assert need >= (64 + 1) * 4
+    assert lib.halo_hadamard_quant_tensor_workspace_bytes(64, 512, 0, 64) >= need + 64 * 512 * 4
+    assert f(None, 0, 64, 512, 512, 0, 512, 0, Q, 512, S, W, need, None) == binding.HALO_EINVAL
+    assert f(A, 0, 64, 512, 512, 0, 48, 0, Q, 512, S, W, need, None) == binding.HALO_ESHAPE
+    assert f(A, 0, 64, 512, 512, 0, 512, 0, Q, 512, S, None, 0, None) == binding.HALO_EWORKSPACE
+    assert f(A, 0, 64, 512, 512, 0, 512, 0, Q, 512, S, W, need - 1, None) == binding.HALO_EWORKSPACE
+    assert f(A, 0, 64, 512, 512, 1, 512, 0, Q, 64, S, W, 1 << 20, None) == binding.HALO_EUNSUPPORTED
+    assert f(A, 0, 64, 512, 512, 0, 0, 0, Q, 520, S, W, need, None) == binding.HALO_EALIGN
+    assert f(None, 0, 0, 512, 512, 0, 0, 0, None, 512, None, None, 0, None) == binding.HALO_OK
+    bad_mode = binding.make_desc(64, 64, 64, 1, scale_mode=5)
+    P = _p(0x1000)
+    assert lib.halo_linear_fwd(ctypes.byref(bad_mode), P, P, P, P, P, P, P, None, 0, None) == binding.HALO_EINVAL
+    per_tensor = binding.make_desc(64, 64, 64, 1, scale_mode=binding.HALO_SCALE_PER_TENSOR)
+    assert lib.halo_linear_fwd(ctypes.byref(per_tensor), P, P, P, P, P, P, P, None, 0, None) == binding.HALO_EWORKSPACE
+    assert binding.halo_linear_workspace_bytes(per_tensor) > binding.halo_linear_workspace_bytes(binding.make_desc(64, 64, 64, 1))
 
 
 def test_binding_refuses_missing_library(tmp_path):
