@@ -207,6 +207,29 @@ halo_status halo_gemm_i8_pair(const halo_gemm_desc* g1, const halo_gemm_desc* g2
 halo_status halo_mfma_i8_probe(const int8_t* operands, int32_t iters, int32_t* sink, void* stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * MXFP6 variant of the forward product (Section 4 "Setup": FP6 E3M2 elements; Appendix "MXFP6": microscaling; the
+ * paper names the formats only, the arithmetic below is the public OCP Microscaling Formats specification's).
+ *
+ * halo_mx6_quant: rotate -> per-block scale -> FP6.   in bf16 [rows x cols] (ld_in elements), cols a multiple of 32.
+ *   v = in (I (x) H_had_block) as in halo_hadamard_quant.  Every block of 32 consecutive elements of a row shares the
+ *   scale 2^(floor(log2(max |v|)) - 4), stored as an E8M0 byte (exponent + 127; an all-zero block: 127) in
+ *   out_scales[r * ld_scales + k/32].  Elements are v / scale rounded to the nearest E3M2 value (1 sign, 3 exponent
+ *   bits with bias 3, 2 mantissa bits; ties to the even mantissa, saturating at +-28, zero stored as +0) and packed
+ *   least-significant element first, 24 bytes per block, in out_codes[r * ld_codes + (k/32) * 24 ...] (ld_codes in
+ *   bytes, a multiple of 8).
+ * halo_gemm_mx6: C[M x N] = A[M x K] B[N x K]^T on such operands (both K-contiguous, K a multiple of 128), fp32
+ *   accumulation in the matrix cores (v_mfma_scale_f32_16x16x128_f8f6f4), C bf16 or fp32 with leading dimension ldc
+ *   (elements).  The accumulation order is the hardware's: results agree with an exact evaluation to fp32 rounding
+ *   of the partial sums, not bit for bit.
+ */
+halo_status halo_mx6_quant(const void* in, int64_t rows, int64_t cols, int64_t ld_in, int32_t had_block,
+                           uint8_t* out_codes, int64_t ld_codes, uint8_t* out_scales, int64_t ld_scales, void* stream);
+
+halo_status halo_gemm_mx6(const uint8_t* A, int64_t lda, const uint8_t* scales_a, int64_t ld_scales_a, const uint8_t* B,
+                          int64_t ldb, const uint8_t* scales_b, int64_t ld_scales_b, int64_t M, int64_t N, int64_t K,
+                          void* C, halo_dtype c_dt, int64_t ldc, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
  * halo_dequant_unrotate: the tail of both backward products.   (Table "HALO levels": the trailing H^T
  * of  (E_Y)_Q (WH)_Q H^T  and  (E_Y^T)_Q (XH)_Q H^T,  and the leading H^T of level 2.)
  *

@@ -30,6 +30,7 @@ EXPORTED_SYMBOLS = (
     "halo_quant_dual_workspace_bytes", "halo_quant_dual",
     "halo_quant_dual_static_max_workspace_bytes", "halo_quant_dual_static",
     "halo_gemm_i8", "halo_gemm_i8_desc", "halo_gemm_i8_pair", "halo_mfma_i8_probe",
+    "halo_mx6_quant", "halo_gemm_mx6",
     "halo_dequant_unrotate_workspace_bytes", "halo_dequant_unrotate",
     "halo_linear_workspace_bytes", "halo_linear_fwd", "halo_linear_bwd",
 )
@@ -99,6 +100,10 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.halo_gemm_i8_desc.argtypes = [c.POINTER(GemmDesc), vp]
     lib.halo_mfma_i8_probe.restype = c.c_int
     lib.halo_mfma_i8_probe.argtypes = [vp, i32, vp, vp]
+    lib.halo_mx6_quant.restype = c.c_int
+    lib.halo_mx6_quant.argtypes = [vp, i64, i64, i64, i32, vp, i64, vp, i64, vp]
+    lib.halo_gemm_mx6.restype = c.c_int
+    lib.halo_gemm_mx6.argtypes = [vp, i64, vp, i64, vp, i64, vp, i64, i64, i64, i64, vp, c.c_int, i64, vp]
     lib.halo_dequant_unrotate_workspace_bytes.restype = sz
     lib.halo_dequant_unrotate_workspace_bytes.argtypes = [i64, i64, i32]
     lib.halo_dequant_unrotate.restype = c.c_int
@@ -303,6 +308,39 @@ def halo_mfma_i8_probe(operands: torch.Tensor, iters: int, sink: Optional[torch.
     st = load_library().halo_mfma_i8_probe(_ptr(operands), int(iters), _ptr(sink), _stream())
     _check(st, "halo_mfma_i8_probe")
     return 256.0 * 8 * iters * 16 * 65536.0
+
+
+def halo_mx6_quant(x: torch.Tensor, *, had_block: int = 0, out_codes: Optional[torch.Tensor] = None,
+                   out_scales: Optional[torch.Tensor] = None) -> Tuple[torch.Tensor, torch.Tensor]:
+    """rotate -> E8M0 scale per 32 elements -> packed FP6 E3M2.  Returns (codes uint8 [rows, cols/32*24],
+    scales uint8 [rows, cols/32])."""
+    _need_cuda(x, out_codes, out_scales)
+    assert x.dim() == 2 and x.stride(1) == 1 and x.dtype == torch.bfloat16
+    rows, cols = x.shape
+    if out_codes is None:
+        out_codes = torch.empty((rows, cols // 32 * 24), dtype=torch.uint8, device=x.device)
+    if out_scales is None:
+        out_scales = torch.empty((rows, cols // 32), dtype=torch.uint8, device=x.device)
+    st = load_library().halo_mx6_quant(_ptr(x), rows, cols, x.stride(0) if rows else cols, had_block, _ptr(out_codes),
+                                       out_codes.stride(0) if rows else 24, _ptr(out_scales),
+                                       out_scales.stride(0) if rows else 1, _stream())
+    _check(st, "halo_mx6_quant")
+    return out_codes, out_scales
+
+
+def halo_gemm_mx6(a: torch.Tensor, sa: torch.Tensor, b: torch.Tensor, sb: torch.Tensor, *,
+                  out_dtype: torch.dtype = torch.float32, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """C = A B^T on packed MXFP6 operands (codes [rows, K/32*24] uint8, scales [rows, K/32] uint8)."""
+    _need_cuda(a, sa, b, sb, out)
+    M, N, K = a.shape[0], b.shape[0], sa.shape[1] * 32
+    assert a.shape[1] == K // 32 * 24 and b.shape[1] == K // 32 * 24 and sb.shape[1] * 32 == K
+    if out is None:
+        out = _empty_padded(M, N, out_dtype, a.device)
+    st = load_library().halo_gemm_mx6(_ptr(a), a.stride(0) if M else 24, _ptr(sa), sa.stride(0) if M else 4, _ptr(b),
+                                      b.stride(0) if N else 24, _ptr(sb), sb.stride(0) if N else 4, M, N, K, _ptr(out),
+                                      _dt(out.dtype), out.stride(0) if M else N, _stream())
+    _check(st, "halo_gemm_mx6")
+    return out
 
 
 def halo_dequant_unrotate(acc: torch.Tensor, row_scale: Optional[torch.Tensor], *, had_block: int = 0,

@@ -345,6 +345,48 @@ halo_status halo_gemm_i8_pair(const halo_gemm_desc* g1, const halo_gemm_desc* g2
 }
 
 // ------------------------------------------------------------------------------------------------
+halo_status halo_mx6_quant(const void* in, int64_t rows, int64_t cols, int64_t ld_in, int32_t had_block,
+                           uint8_t* out_codes, int64_t ld_codes, uint8_t* out_scales, int64_t ld_scales, void* stream) {
+    if (rows < 0 || cols < 0) return HALO_EINVAL;
+    if (rows == 0 || cols == 0) return HALO_OK;
+    if (!in || !out_codes || !out_scales) return HALO_EINVAL;
+    if (rows > kMaxDim || cols > kMaxRowCols) return HALO_EUNSUPPORTED;
+    if (cols % 32) return HALO_ESHAPE;
+    if (ld_in < cols || ld_codes < cols / 32 * 24 || ld_scales < cols / 32) return HALO_ESHAPE;
+    if (!aligned16(in) || !aligned16(out_codes) || (ld_in * 2) % 16 || ld_codes % 8) return HALO_EALIGN;
+    const halo_status st = check_block(had_block, cols, kMaxRightBlock);
+    if (st != HALO_OK) return st;
+    RowArgs r{};
+    r.in = in; r.ld_in = ld_in; r.rows = rows; r.cols = cols; r.out = out_codes; r.ld_out = ld_codes;
+    r.mx_scales = out_scales; r.ld_mx_scales = ld_scales;
+    r.log_block = had_block ? ilog2_exact(had_block) : 0;
+    return from_hip(launch_row_transform(r, IN_BF16, OUT_MX6, reinterpret_cast<hipStream_t>(stream)));
+}
+
+halo_status halo_gemm_mx6(const uint8_t* A, int64_t lda, const uint8_t* scales_a, int64_t ld_scales_a, const uint8_t* B,
+                          int64_t ldb, const uint8_t* scales_b, int64_t ld_scales_b, int64_t M, int64_t N, int64_t K,
+                          void* C, halo_dtype c_dt, int64_t ldc, void* stream) {
+    if (M < 0 || N < 0 || K < 0) return HALO_EINVAL;
+    if (c_dt != HALO_BF16 && c_dt != HALO_F32) return HALO_EINVAL;
+    if (M == 0 || N == 0) return HALO_OK;
+    if (!C) return HALO_EINVAL;
+    if (K > 0 && (!A || !B || !scales_a || !scales_b)) return HALO_EINVAL;
+    if (M > kMaxDim || N > kMaxDim || K > kMaxDim) return HALO_EUNSUPPORTED;
+    if (K % 128) return HALO_ESHAPE;
+    if (ldc < N) return HALO_ESHAPE;
+    if (K > 0) {
+        if (lda < K / 32 * 24 || ldb < K / 32 * 24 || ld_scales_a < K / 32 || ld_scales_b < K / 32) return HALO_ESHAPE;
+        if (!aligned16(A) || !aligned16(B) || lda % 8 || ldb % 8) return HALO_EALIGN;
+        if ((reinterpret_cast<uintptr_t>(scales_a) & 3u) || (reinterpret_cast<uintptr_t>(scales_b) & 3u) ||
+            ld_scales_a % 4 || ld_scales_b % 4)
+            return HALO_EALIGN;
+    }
+    if (!aligned16(C)) return HALO_EALIGN;
+    Mx6GemmArgs g{A, lda, scales_a, ld_scales_a, B, ldb, scales_b, ld_scales_b, M, N, K, C, c_dt == HALO_F32 ? 1 : 0, ldc};
+    return from_hip(launch_gemm_mx6(g, reinterpret_cast<hipStream_t>(stream)));
+}
+
+// ------------------------------------------------------------------------------------------------
 size_t halo_dequant_unrotate_workspace_bytes(int64_t rows, int64_t cols, int32_t had_block_left) {
     if (rows <= 0 || cols <= 0 || had_block_left <= 0) return 0;
     return round256((size_t)rows * (size_t)cols * 4);

@@ -9,7 +9,7 @@
 namespace halo {
 
 enum InKind { IN_BF16 = 0, IN_F32 = 1, IN_I32 = 2 };
-enum OutKind { OUT_Q8 = 0, OUT_BF16 = 1, OUT_F32 = 2 };
+enum OutKind { OUT_Q8 = 0, OUT_BF16 = 1, OUT_F32 = 2, OUT_MX6 = 3 };
 
 // ---- row transform: [pre-scale] -> right-hand FWHT -> [fold] -> {absmax+INT8 | bf16 | fp32} ----
 struct RowArgs {
@@ -28,6 +28,10 @@ struct RowArgs {
     int amax_only;
     const float* given_amax;
     const float* post_scale;
+    // OUT_MX6 only (bf16 input, cols a multiple of 32): `out` receives the packed FP6 E3M2 codes (24 bytes per block of
+    // 32 elements, ld_out in BYTES per row), mx_scales the E8M0 scale bytes [rows x cols/32] with ld_mx_scales bytes per row.
+    uint8_t* mx_scales;
+    int64_t ld_mx_scales;
     // Optional second matrix handled by the same launch (same cols, leading dimensions, fold and block; its own
     // row count and buffers): rows2 == 0 means none.  Saves one launch ramp/tail when two independent tensors get
     // the same treatment (X and W in the forward pass, the two accumulators of the backward pass).
@@ -120,6 +124,17 @@ hipError_t launch_gemm_i8_pair(const GemmArgs& a1, const GemmArgs& a2, hipStream
 bool gemm_config_valid(int cfg, int64_t K);
 // 256 workgroups x 8 wavefronts x iters x 16 MFMAs on the 4 KB of operand bytes at `operands`.
 hipError_t launch_mfma_i8_probe(const int8_t* operands, int iters, int32_t* sink, hipStream_t s);
+
+// ---- MXFP6 GEMM: C[M x N] = A[M x K] B[N x K]^T on packed E3M2 codes with one E8M0 scale per 32 elements along K ----
+struct Mx6GemmArgs {
+    const uint8_t* A; int64_t lda;          // packed codes, bytes per row
+    const uint8_t* SA; int64_t ldsa;        // scale bytes, bytes per row
+    const uint8_t* B; int64_t ldb;
+    const uint8_t* SB; int64_t ldsb;
+    int64_t M, N, K;                        // K a multiple of 128
+    void* C; int c_is_f32; int64_t ldc;     // elements
+};
+hipError_t launch_gemm_mx6(const Mx6GemmArgs& a, hipStream_t s);
 
 inline int ilog2_exact(int64_t v) {
     int l = 0;

@@ -311,6 +311,52 @@ __device__ __forceinline__ void row_phase2(const RowArgs& a, const RowCtx& x, co
                     if (k0 + e < a.cols) orow[k0 + e] = (int8_t)((packed[e / 4] >> (8 * (e & 3))) & 0xFF);
             }
         }
+    } else if constexpr (OUT == OUT_MX6) {
+        // Microscaling FP6: the four lanes of a quad hold one block of 32 consecutive elements.  Shared scale
+        // 2^(floor(log2(block absmax)) - 4) (E8M0), elements rounded to E3M2 (ties to even mantissa, saturating at 28),
+        // eight 6-bit codes per lane packed least-significant first; the quad's 24 bytes leave as 8 + 4 + 8 + 4.
+        static_assert(EPL == 8, "MXFP6 output takes bf16 input");
+        unsigned char* orow = reinterpret_cast<unsigned char*>(a.out) + x.row * a.ld_out;
+        const int j = x.lane & 3;
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) {
+            const int64_t k0 = x.kbase + (int64_t)c * 64 * EPL;
+            float bm = 0.0f;
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) bm = __builtin_fmaxf(bm, fabsf(v[c * EPL + e]));
+            bm = __builtin_fmaxf(bm, lane_xor<0>(bm, x.bperm_addr));
+            bm = __builtin_fmaxf(bm, lane_xor<1>(bm, x.bperm_addr));
+            int shared = (int)(__float_as_uint(bm) >> 23) - 127 - 4;
+            shared = shared < -127 ? -127 : shared;               // the upper clamp cannot bind: exponent <= 127 - 4
+            if (!(bm > 0.0f)) shared = 0;
+            uint32_t code[EPL];
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) {
+                const float xs = __builtin_ldexpf(v[c * EPL + e], -shared);
+                const float ax = fabsf(xs);
+                uint32_t bits = __float_as_uint(ax);
+                bits += 0x000FFFFFu + ((bits >> 21) & 1u);          // round to two mantissa bits, ties to even
+                uint32_t q = (bits >> 21) - (124u << 2);            // [exponent + 3 | mantissa]
+                q = q > 31u ? 31u : q;
+                const uint32_t sub = (uint32_t)__builtin_rintf(ax * 16.0f);     // below the smallest normal: steps of 2^-4
+                q = ax < 0.25f ? sub : q;
+                code[e] = q | ((q != 0u && xs < 0.0f) ? 32u : 0u);
+            }
+            const uint32_t w0 = code[0] | (code[1] << 6) | (code[2] << 12) | (code[3] << 18) | (code[4] << 24) | (code[5] << 30);
+            const uint32_t w1 = (code[5] >> 2) | (code[6] << 4) | (code[7] << 10);
+            const uint32_t nb_w0 = (uint32_t)__builtin_amdgcn_mov_dpp((int)w0, 0xF9, 0xF, 0xF, true);   // quad_perm [1,2,3,3]
+            if (FAST || (x.row_ok && k0 + EPL <= a.cols)) {
+                unsigned char* blk = orow + (k0 >> 5) * 24;          // k0 >> 5 is the same for the four lanes of the quad
+                if ((j & 1) == 0) {
+                    uint32_t* dst = reinterpret_cast<uint32_t*>(blk + 12 * (j >> 1));
+                    dst[0] = w0;
+                    dst[1] = w1 | (nb_w0 << 16);
+                } else {
+                    *reinterpret_cast<uint32_t*>(blk + 8 + 12 * (j >> 1)) = (w0 >> 16) | (w1 << 16);
+                }
+                if (j == 0) a.mx_scales[x.row * a.ld_mx_scales + (k0 >> 5)] = (uint8_t)(shared + 127);
+            }
+        }
     } else if constexpr (OUT == OUT_BF16) {
         uint16_t* orow = reinterpret_cast<uint16_t*>(a.out) + x.row * a.ld_out;
 #pragma unroll
@@ -487,6 +533,7 @@ hipError_t launch_row_transform(const RowArgs& a, InKind in, OutKind out, hipStr
     if (in == IN_F32 && out == OUT_Q8) return launch_by_seg<IN_F32, OUT_Q8>(a, s);
     if (in == IN_I32 && out == OUT_BF16) return launch_by_seg<IN_I32, OUT_BF16>(a, s);
     if (in == IN_I32 && out == OUT_F32) return launch_by_seg<IN_I32, OUT_F32>(a, s);
+    if (in == IN_BF16 && out == OUT_MX6) return a.cols % 32 == 0 ? launch_by_seg<IN_BF16, OUT_MX6>(a, s) : hipErrorInvalidValue;
     return hipErrorInvalidValue;
 }
 

@@ -157,6 +157,9 @@ CONFIGS: Dict[str, LayerConfig] = {
         LinearShape("up", 14336, 4096, shares_input_with="gate"),
         LinearShape("down", 4096, 14336),
     ), level=2, outlier_frac=0.001, backward=True),
+    # MXFP6 variant: 8192 x 4096 . 4096 x 4096, FP6 E3M2 with an E8M0 scale per 32 along K after the rotation, forward product.
+    "c5": LayerConfig("c5", 8192, (LinearShape("proj", 4096, 4096),), level=1,
+                      outlier_frac=0.001, backward=False, seed=5),
 }
 
 

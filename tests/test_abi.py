@@ -182,6 +182,24 @@ def test_hadamard_quant_tensor_argument_errors(lib):
     assert binding.halo_linear_workspace_bytes(per_tensor) > binding.halo_linear_workspace_bytes(binding.make_desc(64, 64, 64, 1))
 
 
+def test_mx6_argument_errors(lib):
+    q, g = lib.halo_mx6_quant, lib.halo_gemm_mx6
+    A, Cq, S, B, C = _p(0x1000), _p(0x2000), _p(0x3000), _p(0x4000), _p(0x5000)
+    assert q(None, 64, 512, 512, 512, Cq, 384, S, 16, None) == binding.HALO_EINVAL
+    assert q(A, 64, 500, 512, 0, Cq, 384, S, 16, None) == binding.HALO_ESHAPE          # cols % 32
+    assert q(A, 64, 512, 512, 0, Cq, 380, S, 16, None) == binding.HALO_ESHAPE          # ld_codes < cols/32*24
+    assert q(A, 64, 512, 512, 0, Cq, 388, S, 16, None) == binding.HALO_EALIGN          # ld_codes % 8
+    assert q(A, 64, 512, 512, 48, Cq, 384, S, 16, None) == binding.HALO_ESHAPE         # block not a power of two
+    assert q(None, 0, 512, 512, 0, None, 384, None, 16, None) == binding.HALO_OK
+    assert g(A, 96, S, 4, B, 96, S, 4, 64, 64, 128, None, 1, 64, None) == binding.HALO_EINVAL
+    assert g(A, 96, S, 4, B, 96, S, 4, 64, 64, 96, C, 1, 64, None) == binding.HALO_ESHAPE      # K % 128
+    assert g(A, 90, S, 4, B, 96, S, 4, 64, 64, 128, C, 1, 64, None) == binding.HALO_ESHAPE     # lda too small
+    assert g(A, 100, S, 4, B, 96, S, 4, 64, 64, 128, C, 1, 64, None) == binding.HALO_EALIGN    # lda % 8
+    assert g(A, 96, S, 6, B, 96, S, 4, 64, 64, 128, C, 1, 64, None) == binding.HALO_EALIGN     # scale pitch % 4
+    assert g(A, 96, S, 4, B, 96, S, 4, 64, 64, 128, C, 7, 64, None) == binding.HALO_EINVAL
+    assert g(None, 0, None, 0, None, 0, None, 0, 0, 64, 128, None, 1, 64, None) == binding.HALO_OK
+
+
 def test_binding_refuses_missing_library(tmp_path):
     with pytest.raises(RuntimeError):
         binding.load_library(str(tmp_path / "nope.so"))
