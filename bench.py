@@ -11,7 +11,7 @@ quantisation and Hadamard overheads included).  `roofline` describes the kernel 
 that step; `kernels` lists every kernel family with its own roofline fraction; `cpu_baseline` is the numpy
 oracle timed on the host cores.  `configs` carries the same kind of record for c3 (MLP down projection, HALO-2)
 and c4 (the seven linears of a decoder layer at 8192 tokens: seven forwards, then seven backwards, back to back
-on one stream, q/k/v and gate/up sharing one quantised activation).  `mfma_ceiling` is the INT8 MFMA rate the
+on one stream, q/k/v and gate/up sharing one quantised activation), and for c5, the MXFP6 forward product.  `mfma_ceiling` is the INT8 MFMA rate the
 machine sustains on constant, on random and on the step's own operand bytes with nothing else running
 (halo_mfma_i8_probe); `copy_GBs` a plain device copy, the practical HBM ceiling.
 """
@@ -36,7 +36,7 @@ def parse():
     p.add_argument("--steps", type=int, default=100)
     p.add_argument("--warmup", type=int, default=20)
     p.add_argument("--config", default="c2", help="headline workload: c2 (default) or c3")
-    p.add_argument("--extra-configs", default="c3,c4", help="comma list of further configs reported under `configs`")
+    p.add_argument("--extra-configs", default="c3,c4,c5", help="comma list of further configs reported under `configs`")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--kernel-iters", type=int, default=50, help="launches per kernel for the per-kernel timings")
     p.add_argument("--pmc-target", default="",
@@ -348,6 +348,59 @@ def run_layer(key, args, dev, with_oracle):
     return rec
 
 
+def run_mx6(key, args, dev, copy_gbs, with_oracle):
+    """Config c5: the MXFP6 forward product (rotate + microscaling FP6 quantise of X and W, scaled-MFMA GEMM)."""
+    import numpy as np
+    import torch
+    from paper_2501_02625_amd import binding, inputs
+    cfg = inputs.CONFIGS[key]
+    lin = cfg.linears[0]
+    b, m, n = cfg.tokens, lin.m, lin.n
+    hm = min(m & -m, 4096)
+    to_dev = lambda bits: torch.from_numpy(bits.view(np.int16)).to(dev).view(torch.bfloat16)
+    X = to_dev(inputs.make_activations(b, m, cfg.outlier_frac, cfg.seed))
+    W = to_dev(inputs.make_weights(n, m, cfg.seed))
+    xc = torch.empty((b, m // 32 * 24), dtype=torch.uint8, device=dev); xs = torch.empty((b, m // 32), dtype=torch.uint8, device=dev)
+    wc = torch.empty((n, m // 32 * 24), dtype=torch.uint8, device=dev); ws = torch.empty((n, m // 32), dtype=torch.uint8, device=dev)
+    Y = torch.empty((b, n), dtype=torch.bfloat16, device=dev)
+
+    def step():
+        binding.halo_mx6_quant(X, had_block=hm, out_codes=xc, out_scales=xs)
+        binding.halo_mx6_quant(W, had_block=hm, out_codes=wc, out_scales=ws)
+        binding.halo_gemm_mx6(xc, xs, wc, ws, out=Y)
+    ms = time_steps(step, args.steps, args.warmup)
+    ops = 2.0 * b * m * n
+    it = args.kernel_iters
+    kernels = []
+    for nm, T, rows, oc, osc in (("mx6_quant(X)", X, b, xc, xs), ("mx6_quant(W)", W, n, wc, ws)):
+        kms = time_launches(lambda: binding.halo_mx6_quant(T, had_block=hm, out_codes=oc, out_scales=osc), it)
+        nbytes = rows * m * (2 + 0.75) + rows * (m // 32)
+        gbs = nbytes / (kms * 1e-3) / 1e9
+        kernels.append(dict(name=nm, bound="hbm", ms=kms, achieved=gbs, peak=HBM_PEAK_GBS, unit="GB/s", frac=gbs / HBM_PEAK_GBS,
+                            frac_of_copy=gbs / copy_gbs if copy_gbs else None, bytes=nbytes))
+    kms = time_launches(lambda: binding.halo_gemm_mx6(xc, xs, wc, ws, out=Y), it)
+    tf = ops / (kms * 1e-3) / 1e12
+    kernels.append(dict(name="gemm_mx6(Xc,Wc)->Y", bound="mfma", ms=kms, achieved=tf, peak=10100.0, unit="TFLOP/s",
+                        frac=tf / 10100.0, shape=[b, n, m]))
+    rec = dict(workload="%s: MXFP6 forward product, X %dx%d, W %dx%d, FWHT over K, FP6 E3M2 elements with an E8M0 scale "
+                        "per 32 along K, fp32 accumulation, bf16 in/out" % (key, b, m, n, m),
+               b=b, m=m, n=n, ops_per_step=ops, ms_per_step=ms, value=ops / (ms * 1e-3) / 1e12, unit="TFLOP/s",
+               kernels=kernels)
+    if with_oracle:
+        from oracle import mxfp6_oracle as mxo
+        from oracle import halo_oracle as orc
+        tokens = 256
+        Xr = orc.bf16_bits_to_real(inputs.make_activations(tokens, m, cfg.outlier_frac, cfg.seed))
+        Wr = orc.bf16_bits_to_real(inputs.make_weights(n, m, cfg.seed))
+        c0 = time.perf_counter()
+        mxo.forward_mxfp6(Xr, Wr, hm)
+        secs = time.perf_counter() - c0
+        rec["cpu_baseline"] = dict(value=2.0 * tokens * m * n / secs / 1e12, unit="TFLOP/s", cores=blas_threads(), kind="oracle",
+                                   seconds=secs, sample="the first %d of %d tokens against the full weight matrix, "
+                                   "extrapolated by operation count (numpy oracle)" % (tokens, b))
+    return rec
+
+
 def measure_copy(dev):
     import torch
     src = torch.empty((256 << 20,), dtype=torch.uint8, device=dev)
@@ -447,7 +500,9 @@ def main():
         del L
         L = None
         torch.cuda.empty_cache()
-        if len(cfg.linears) == 1:
+        if key == "c5":
+            r = run_mx6(key, args, dev, copy_gbs, not args.no_cpu_baseline)
+        elif len(cfg.linears) == 1:
             r, Lx, _ = run_single(key, args, dev, copy_gbs, True, not args.no_cpu_baseline)
             del Lx
         else:

@@ -217,7 +217,8 @@ halo_status halo_mfma_i8_probe(const int8_t* operands, int32_t iters, int32_t* s
  *   bits with bias 3, 2 mantissa bits; ties to the even mantissa, saturating at +-28, zero stored as +0) and packed
  *   least-significant element first, 24 bytes per block, in out_codes[r * ld_codes + (k/32) * 24 ...] (ld_codes in
  *   bytes, a multiple of 8).
- * halo_gemm_mx6: C[M x N] = A[M x K] B[N x K]^T on such operands (both K-contiguous, K a multiple of 128), fp32
+ * halo_gemm_mx6: C[M x N] = A[M x K] B[N x K]^T on such operands (both K-contiguous, K a multiple of 128, leading
+ *   dimensions of the code matrices multiples of 16 bytes, of the scale matrices multiples of 4), fp32
  *   accumulation in the matrix cores (v_mfma_scale_f32_16x16x128_f8f6f4), C bf16 or fp32 with leading dimension ldc
  *   (elements).  The accumulation order is the hardware's: results agree with an exact evaluation to fp32 rounding
  *   of the partial sums, not bit for bit.

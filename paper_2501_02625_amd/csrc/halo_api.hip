@@ -376,7 +376,7 @@ halo_status halo_gemm_mx6(const uint8_t* A, int64_t lda, const uint8_t* scales_a
     if (ldc < N) return HALO_ESHAPE;
     if (K > 0) {
         if (lda < K / 32 * 24 || ldb < K / 32 * 24 || ld_scales_a < K / 32 || ld_scales_b < K / 32) return HALO_ESHAPE;
-        if (!aligned16(A) || !aligned16(B) || lda % 8 || ldb % 8) return HALO_EALIGN;
+        if (!aligned16(A) || !aligned16(B) || lda % 16 || ldb % 16) return HALO_EALIGN;
         if ((reinterpret_cast<uintptr_t>(scales_a) & 3u) || (reinterpret_cast<uintptr_t>(scales_b) & 3u) ||
             ld_scales_a % 4 || ld_scales_b % 4)
             return HALO_EALIGN;

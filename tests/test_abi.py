@@ -194,7 +194,7 @@ def test_mx6_argument_errors(lib):
     assert g(A, 96, S, 4, B, 96, S, 4, 64, 64, 128, None, 1, 64, None) == binding.HALO_EINVAL
     assert g(A, 96, S, 4, B, 96, S, 4, 64, 64, 96, C, 1, 64, None) == binding.HALO_ESHAPE      # K % 128
     assert g(A, 90, S, 4, B, 96, S, 4, 64, 64, 128, C, 1, 64, None) == binding.HALO_ESHAPE     # lda too small
-    assert g(A, 100, S, 4, B, 96, S, 4, 64, 64, 128, C, 1, 64, None) == binding.HALO_EALIGN    # lda % 8
+    assert g(A, 104, S, 4, B, 96, S, 4, 64, 64, 128, C, 1, 64, None) == binding.HALO_EALIGN    # lda % 16
     assert g(A, 96, S, 6, B, 96, S, 4, 64, 64, 128, C, 1, 64, None) == binding.HALO_EALIGN     # scale pitch % 4
     assert g(A, 96, S, 4, B, 96, S, 4, 64, 64, 128, C, 7, 64, None) == binding.HALO_EINVAL
     assert g(None, 0, None, 0, None, 0, None, 0, 0, 64, 128, None, 1, 64, None) == binding.HALO_OK
