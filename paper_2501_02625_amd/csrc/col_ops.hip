@@ -313,7 +313,7 @@ col_quant_t_kernel(const uint16_t* in, int64_t ld_in, int64_t rows, int64_t cols
 //   cols:  EqT [n x b] = Q_row( (E[i,j] * fold_r[i])^T ) (the saved activation scales folded in; feeds G = E^T X)
 // Pass 1 writes the partial maxima of both absmax vectors per tile (no atomics); pass 2 reduces the partials it needs,
 // re-reads E (cache-hot), emits the row-wise codes directly and the column-wise codes through an LDS transpose.
-constexpr int kAR = 32, kAC = 256;                               // absmax pass: tile rows, tile columns
+constexpr int kAC = 256;                                         // absmax pass: tile columns (tile rows: 32 per round)
 constexpr int kDR = 128, kDC = 128, kDPitch = kDR / 4 + 1;     // quantising pass: tile rows, columns, LDS dwords per column
 
 __device__ __forceinline__ float max_across_32(float x) {
@@ -326,60 +326,72 @@ __device__ __forceinline__ float max_across_32(float x) {
     return x;
 }
 
-// Loads the 4 x 8 block (row quad iq, 8 columns from col) of E as fp32; out-of-range elements are zero.
-__device__ __forceinline__ void load_block(const uint16_t* in, int64_t ld_in, int64_t rows, int64_t cols, int64_t row0,
-                                           int64_t col, float (&x)[4][8]) {
-    const bool full = col + 8 <= cols;
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        const int64_t row = row0 + r;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) x[r][e] = 0.0f;
-        if (row < rows && col < cols) {
-            const uint16_t* src = in + row * ld_in + col;
-            if (full) {
-                const uint4 w = *reinterpret_cast<const uint4*>(src);
-                const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    x[r][2 * i] = __uint_as_float(ww[i] << 16);
-                    x[r][2 * i + 1] = __uint_as_float(ww[i] & 0xFFFF0000u);
-                }
-            } else {
-                for (int e = 0; e < 8; ++e)
-                    if (col + e < cols) x[r][e] = __uint_as_float((uint32_t)src[e] << 16);
-            }
+// The 8 bf16 of E at (row, col .. col+7) as four dwords; out-of-range elements are zero.
+__device__ __forceinline__ uint4 load_row8(const uint16_t* __restrict__ in, int64_t ld_in, int64_t rows, int64_t cols,
+                                           int64_t row, int64_t col) {
+    uint4 w = make_uint4(0u, 0u, 0u, 0u);
+    if (row < rows && col < cols) {
+        const uint16_t* src = in + row * ld_in + col;
+        if (col + 8 <= cols) {
+            w = *reinterpret_cast<const uint4*>(src);
+        } else {
+            uint32_t h[8];
+            for (int e = 0; e < 8; ++e) h[e] = col + e < cols ? (uint32_t)src[e] : 0u;
+            w = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
         }
+    }
+    return w;
+}
+
+__device__ __forceinline__ void widen_row8(const uint4& w, float (&x)[8]) {
+    const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        x[2 * i] = __uint_as_float(ww[i] << 16);
+        x[2 * i + 1] = __uint_as_float(ww[i] & 0xFFFF0000u);
     }
 }
 
-// Pass 1: every workgroup writes the partial maxima of its 32 x 256 tile (no atomics: device-scope atomics are
-// resolved beyond the per-XCD L2 and cost more than the whole pass): row_part[row][column tile], col_part[row tile][col].
+// Pass 1: every workgroup writes the partial maxima of its (32 * ROUNDS) x 256 tile (no atomics: device-scope atomics
+// are resolved beyond the per-XCD L2 and cost more than the whole pass): row_part[row][column tile],
+// col_part[row tile][col].  A thread owns 8 columns of 4 * ROUNDS rows and issues all its loads before the first use;
+// taller tiles leave pass 2 fewer partial maxima to reduce, shorter ones fill the chip when E is small.
+template <int ROUNDS>
 __global__ void __launch_bounds__(256)
-dual_amax_kernel(const uint16_t* in, int64_t ld_in, int64_t rows, int64_t cols, const float* fold_c, const float* fold_r,
-                 float* row_part, float* col_part) {
+dual_amax_kernel(const uint16_t* __restrict__ in, int64_t ld_in, int64_t rows, int64_t cols,
+                 const float* __restrict__ fold_c, const float* __restrict__ fold_r, float* __restrict__ row_part,
+                 float* __restrict__ col_part) {
     __shared__ float s_col[8][kAC];
     const int tid = threadIdx.x, lane = tid & 63;
-    const int jl = tid & 31, rq = tid >> 5;             // 32 column groups of 8, 8 row quads
+    const int jl = tid & 31, rq = tid >> 5;             // 32 column groups of 8, 8 row quads per round of 32 rows
     const int64_t col = (int64_t)blockIdx.x * kAC + 8 * jl;
-    const int64_t row0 = (int64_t)blockIdx.y * kAR + 4 * rq;
+    const int64_t row_base = (int64_t)blockIdx.y * (32 * ROUNDS) + 4 * rq;
+    uint4 raw[ROUNDS][4];
+#pragma unroll
+    for (int s = 0; s < ROUNDS; ++s)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) raw[s][r] = load_row8(in, ld_in, rows, cols, row_base + 32 * s + r, col);
     float fc[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) fc[e] = (fold_c && col + e < cols) ? fold_c[col + e] : 1.0f;
     float cmax[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    float x[4][8];
-    load_block(in, ld_in, rows, cols, row0, col, x);
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        const float fr = (fold_r && row0 + r < rows) ? fold_r[row0 + r] : 1.0f;
-        float rmax = 0.0f;
+    for (int s = 0; s < ROUNDS; ++s) {
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            rmax = fmaxf(rmax, fabsf(x[r][e] * fc[e]));
-            cmax[e] = fmaxf(cmax[e], fabsf(x[r][e] * fr));
+        for (int r = 0; r < 4; ++r) {
+            const int64_t row = row_base + 32 * s + r;
+            const float fr = (fold_r && row < rows) ? fold_r[row] : 1.0f;
+            float x[8];
+            widen_row8(raw[s][r], x);
+            float rmax = 0.0f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                rmax = fmaxf(rmax, fabsf(x[e] * fc[e]));
+                cmax[e] = fmaxf(cmax[e], fabsf(x[e] * fr));
+            }
+            rmax = max_across_32(rmax);
+            if ((lane & 31) == 0 && row < rows) row_part[row * gridDim.x + blockIdx.x] = rmax;
         }
-        rmax = max_across_32(rmax);
-        if ((lane & 31) == 0 && row0 + r < rows) row_part[(row0 + r) * gridDim.x + blockIdx.x] = rmax;
     }
 #pragma unroll
     for (int e = 0; e < 8; ++e) s_col[rq][8 * jl + e] = cmax[e];
@@ -394,9 +406,10 @@ dual_amax_kernel(const uint16_t* in, int64_t ld_in, int64_t rows, int64_t cols, 
 }
 
 __global__ void __launch_bounds__(256)
-dual_quant_kernel(const uint16_t* in, int64_t ld_in, int64_t rows, int64_t cols, const float* fold_c, const float* fold_r,
-                  const float* row_part, const float* col_part, int col_tiles, int row_tiles, int8_t* out_q, int64_t ld_q,
-                  float* row_scale, int8_t* out_qt, int64_t ld_qt, float* col_scale) {
+dual_quant_kernel(const uint16_t* __restrict__ in, int64_t ld_in, int64_t rows, int64_t cols,
+                  const float* __restrict__ fold_c, const float* __restrict__ fold_r, const float* __restrict__ row_part,
+                  const float* __restrict__ col_part, int col_tiles, int row_tiles, int8_t* __restrict__ out_q, int64_t ld_q,
+                  float* __restrict__ row_scale, int8_t* __restrict__ out_qt, int64_t ld_qt, float* __restrict__ col_scale) {
     __shared__ uint32_t s_tile[kDC * kDPitch];
     __shared__ float s_red[2][2][128];     // [row/col][half][index]
     __shared__ float s_amax_c[kDC], s_amax_r[kDR];
@@ -404,8 +417,14 @@ dual_quant_kernel(const uint16_t* in, int64_t ld_in, int64_t rows, int64_t cols,
     const int jl = tid & 15, rq = tid >> 4;             // 16 column groups of 8, 16 row quads (two rounds)
     const int64_t j0 = (int64_t)blockIdx.x * kDC, i0 = (int64_t)blockIdx.y * kDR;
     const int64_t col = j0 + 8 * jl;
+    // E first (cache-hot after pass 1): all eight loads of the thread are in flight while the maxima are reduced.
+    uint4 raw[2][4];
+#pragma unroll
+    for (int s = 0; s < 2; ++s)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) raw[s][r] = load_row8(in, ld_in, rows, cols, i0 + 4 * (rq + 16 * s) + r, col);
     // Absmax of this tile's 128 columns and 128 rows from the partial maxima of pass 1 (every workgroup redoes the
-    // reduction it needs: 40 KB of L2 hits instead of one more kernel between the passes).
+    // reduction it needs: a few KB of L2 hits instead of one more kernel between the passes).
     {
         const int o = tid & 127, h = tid >> 7;
         float tc = 0.0f, tr = 0.0f;
@@ -445,7 +464,8 @@ dual_quant_kernel(const uint16_t* in, int64_t ld_in, int64_t rows, int64_t cols,
         const int iq = rq + 16 * s;
         const int64_t row0 = i0 + 4 * iq;
         float x[4][8];
-        load_block(in, ld_in, rows, cols, row0, col, x);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) widen_row8(raw[s][r], x[r]);
         uint32_t bc[4][8];
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
@@ -542,21 +562,31 @@ hipError_t launch_col_fwht(const ColFwhtArgs& a, hipStream_t s) {
     return hipSuccess;
 }
 
+// Rounds of 32 rows per workgroup of the absmax pass: the tallest tile that still gives the chip two workgroups per
+// compute unit.
+static int dual_amax_rounds(int64_t rows, int64_t cols) {
+    const int64_t col_tiles = (cols + kAC - 1) / kAC;
+    for (int r = 4; r > 1; r >>= 1)
+        if (col_tiles * ((rows + 32 * r - 1) / (32 * r)) >= 512) return r;
+    return 1;
+}
+
 size_t dual_quant_workspace_floats(int64_t rows, int64_t cols) {
-    const int64_t col_tiles = (cols + kAC - 1) / kAC, row_tiles = (rows + kAR - 1) / kAR;
+    const int64_t col_tiles = (cols + kAC - 1) / kAC, row_tiles = (rows + 31) / 32;     // sized for one-round tiles
     return (size_t)(rows * col_tiles + row_tiles * cols);
 }
 
 hipError_t launch_dual_quant(const DualQuantArgs& a, hipStream_t s) {
     if (a.rows == 0 || a.cols == 0) return hipSuccess;
-    const int64_t col_tiles = (a.cols + kAC - 1) / kAC, row_tiles = (a.rows + kAR - 1) / kAR;
+    const int rounds = dual_amax_rounds(a.rows, a.cols);
+    const int64_t col_tiles = (a.cols + kAC - 1) / kAC, row_tiles = (a.rows + 32 * rounds - 1) / (32 * rounds);
     float* row_part = a.amax_ws;                                           // [rows][col_tiles]
     float* col_part = row_part + a.rows * col_tiles;                       // [row_tiles][cols]
     const dim3 grid_a((unsigned)col_tiles, (unsigned)row_tiles);
     const dim3 grid((unsigned)((a.cols + kDC - 1) / kDC), (unsigned)((a.rows + kDR - 1) / kDR));
     const uint16_t* in = reinterpret_cast<const uint16_t*>(a.in);
-    hipLaunchKernelGGL(dual_amax_kernel, grid_a, dim3(256), 0, s, in, a.ld_in, a.rows, a.cols, a.fold_c, a.fold_r, row_part,
-                       col_part);
+    auto* amax = rounds == 4 ? dual_amax_kernel<4> : rounds == 2 ? dual_amax_kernel<2> : dual_amax_kernel<1>;
+    hipLaunchKernelGGL(amax, grid_a, dim3(256), 0, s, in, a.ld_in, a.rows, a.cols, a.fold_c, a.fold_r, row_part, col_part);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(dual_quant_kernel, grid, dim3(256), 0, s, in, a.ld_in, a.rows, a.cols, a.fold_c, a.fold_r, row_part,
