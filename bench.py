@@ -36,7 +36,7 @@ def parse():
     p.add_argument("--steps", type=int, default=100)
     p.add_argument("--warmup", type=int, default=20)
     p.add_argument("--config", default="c2", help="headline workload: c2 (default) or c3")
-    p.add_argument("--extra-configs", default="c3,c4,c5", help="comma list of further configs reported under `configs`")
+    p.add_argument("--extra-configs", default="c3,c4,c5,c6", help="comma list of further configs reported under `configs`")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--kernel-iters", type=int, default=50, help="launches per kernel for the per-kernel timings")
     p.add_argument("--pmc-target", default="",
@@ -95,7 +95,7 @@ class Linear:
         self.cfg, self.lin = cfg, cfg.linears[which]
         self.b, self.m, self.n, self.level = cfg.tokens, self.lin.m, self.lin.n, cfg.level
         b, m, n = self.b, self.m, self.n
-        self.hm = min(m & -m, 4096) if self.level >= 1 else 0
+        self.hm = cfg.had_block_m(m) if self.level >= 1 else 0
         self.hb = (b & -b) if self.level >= 2 else 0
         sub = cfg.seed * 1000 + which
         to_dev = lambda bits: torch.from_numpy(bits.view(np.int16)).to(dev).view(torch.bfloat16)
@@ -111,7 +111,7 @@ class Linear:
         self.host["W"] = inputs.make_weights(n, m, sub)
         self.host["E"] = inputs.make_errors(b, n, sub)
         self.W, self.E = to_dev(self.host["W"]), to_dev(self.host["E"])
-        self.desc = binding.make_desc(b, m, n, self.level, torch.bfloat16)
+        self.desc = binding.make_desc(b, m, n, self.level, torch.bfloat16, had_block_m=self.hm)
         self.state = binding.LinearState(Xq, s_x, torch.empty((n, m), dtype=torch.int8, device=dev),
                                          torch.empty((n,), dtype=torch.float32, device=dev))
         alloc = lambda key, shape: (out_bufs.setdefault(key, torch.empty(shape, dtype=torch.bfloat16, device=dev))
@@ -260,7 +260,7 @@ def oracle_slice(cfg, which_list, tokens):
     for which in which_list:
         lin = cfg.linears[which]
         t = inputs.make_linear_inputs(cfg, which, tokens=tokens, need_error=True)
-        hm = min(lin.m & -lin.m, 4096) if cfg.level >= 1 else 0
+        hm = cfg.had_block_m(lin.m) if cfg.level >= 1 else 0
         hb = (tokens & -tokens) if cfg.level >= 2 else 0
         Xr, Wr, Er = (orc.bf16_bits_to_real(t[k]) for k in ("X", "W", "E"))
         c0 = time.perf_counter()

@@ -26,6 +26,15 @@
  *     axis.  H_block is the normalised Walsh-Hadamard matrix of the recursion H_d = H_2 (x) H_{d/2}
  *     (Section 2, "Hadamard Transformations"); its butterflies run in ascending stride order
  *     in fp32 and the 1/sqrt(block) factor is applied once at the end.
+ *   - A right-hand block may also be 28 * 2^n with 64 <= 2^n <= 512 (1792, 3584, 7168, 14336), dividing a row of at
+ *     most 14336 elements: the Kronecker construction H_block = H_{2^n} (x) H_28 of the same section for dimensions
+ *     that are not powers of two (14336 = 512 * 28).  Element i * 28 + j of a block has index i into the Walsh-Hadamard
+ *     factor and j into H_28, the symmetric Hadamard matrix of order 28 of Paley's second construction from the
+ *     quadratic character chi modulo 13: with C = [[0, 1^T], [1, (chi(i - j))]] of order 14, every 0 of C becomes
+ *     [[1, -1], [-1, -1]] and every entry +-1 becomes +-[[1, 1], [1, -1]].  Arithmetic, all fp32: each run of 28
+ *     consecutive elements x becomes x H_28 (every output a running sum over the 28 terms in ascending index order),
+ *     then the butterflies over i in ascending stride order, then one multiply by 1/sqrt(block).  Other sizes, the
+ *     left-hand axis and halo_mx6_quant take power-of-two blocks only (HALO_ESHAPE / HALO_EUNSUPPORTED).
  */
 #ifndef HALO_H
 #define HALO_H
@@ -256,7 +265,8 @@ halo_status halo_dequant_unrotate(const int32_t* acc, int64_t ld_acc, int64_t ro
  *   level 2:  F = (XH)_Q (WH)_Q^T    E = H^T (H E_Y)_Q (WH)_Q H^T        G = (E_Y^T)_Q (XH)_Q H^T
  *
  *   b, m, n        tokens, in-features, out-features.  m and n multiples of 16, b a multiple of 16.
- *   had_block_m    right-hand block over m; 0 = largest power of two dividing m, capped at 4096.
+ *   had_block_m    right-hand block over m; 0 = largest power of two dividing m, capped at 4096 (a Kronecker block
+ *                  28 * 2^n has to be asked for by its size).
  *   had_block_b    left-hand block over b (level 2 only); 0 = largest power of two dividing b.
  *   out_dt         type of Y, E_X and G.
  *   scale_mode     HALO_SCALE_PER_ROW: one scale per row of every GEMM operand; the saved scale vectors are folded

@@ -13,7 +13,7 @@ INCLUDE = os.path.join(ROOT, "include")
 LIB_PATH = os.path.join(PKG_DIR, "libhalo.so")
 BUILD_DIR = os.path.join(PKG_DIR, "_build")
 
-SOURCES = ["halo_api.hip", "row_transform.hip", "col_ops.hip", "gemm_i8.hip", "gemm_mx6.hip"]
+SOURCES = ["halo_api.hip", "row_transform.hip", "col_ops.hip", "gemm_i8.hip", "gemm_mx6.hip", "row_kron.hip"]
 
 # -ffp-contract=off: every fp32 add/mul of the rotation and the quantiser is rounded on its own, which is
 # what makes the INT8 codes reproducible bit for bit.  Packed fp32 instructions are switched off.

@@ -24,6 +24,26 @@ inline halo_status check_block(int32_t block, int64_t len, int64_t cap) {
 
 constexpr int64_t kMaxRightBlock = 4096;
 constexpr int64_t kMaxLeftBlock = 65536;
+
+// Right-hand Hadamard block: what check_block accepts up to 4096, or 28 * 2^n with 64 <= 2^n <= 512 dividing `len`,
+// len <= 14336 (the Kronecker construction H_{2^n} (x) H_28).
+inline halo_status check_right_block(int32_t block, int64_t len) {
+    if (block > 0 && block % 28 == 0 && is_pow2(block / 28)) {
+        if (len % block != 0) return HALO_ESHAPE;
+        return row_kron_shape_ok(len, block) ? HALO_OK : HALO_EUNSUPPORTED;
+    }
+    return check_block(block, len, kMaxRightBlock);
+}
+
+inline void set_right_block(RowArgs& r, int32_t block) {
+    if (block > 0 && !is_pow2(block)) {
+        r.kron_m = 28;
+        r.log_block = ilog2_exact(block / 28);
+    } else {
+        r.kron_m = 0;
+        r.log_block = block ? ilog2_exact(block) : 0;
+    }
+}
 constexpr int64_t kMaxDim = int64_t(1) << 22;   // rows / columns of any matrix argument
 
 struct BwdWorkspace {
@@ -54,7 +74,7 @@ halo_status resolve_desc(const halo_linear_desc* d, int32_t* hm, int32_t* hb) {
     *hb = 0;
     if (d->level >= 1) {
         *hm = d->had_block_m ? d->had_block_m : default_block(d->m, kMaxRightBlock);
-        halo_status st = check_block(*hm, d->m, kMaxRightBlock);
+        halo_status st = check_right_block(*hm, d->m);
         if (st != HALO_OK) return st;
     }
     if (d->level >= 2) {
@@ -129,7 +149,7 @@ halo_status halo_hadamard_quant(const void* in, halo_dtype in_dt, int64_t rows, 
     if (ld_q < (axis == HALO_QUANT_ROWS ? cols : rows)) return HALO_ESHAPE;
     if (!aligned16(in) || !aligned16(out_q) || (ld_in * esz) % 16 || ld_q % 16) return HALO_EALIGN;
     if (fold && !aligned16(fold)) return HALO_EALIGN;
-    halo_status st = check_block(had_block, cols, kMaxRightBlock);
+    halo_status st = check_right_block(had_block, cols);
     if (st != HALO_OK) return st;
     st = check_block(had_block_left, rows, kMaxLeftBlock);
     if (st != HALO_OK) return st;
@@ -147,7 +167,7 @@ halo_status halo_hadamard_quant(const void* in, halo_dtype in_dt, int64_t rows, 
     if (cols > kMaxRowCols) return HALO_EUNSUPPORTED;
     RowArgs r{};
     r.rows = rows; r.cols = cols; r.fold = fold; r.out = out_q; r.ld_out = ld_q; r.out_scale = out_scale;
-    r.log_block = had_block ? ilog2_exact(had_block) : 0;
+    set_right_block(r, had_block);
     if (had_block_left == 0) {
         r.in = in; r.ld_in = ld_in;
         return from_hip(launch_row_transform(r, in_dt == HALO_BF16 ? IN_BF16 : IN_F32, OUT_Q8, s));
@@ -189,7 +209,7 @@ halo_status halo_hadamard_quant_tensor(const void* in, halo_dtype in_dt, int64_t
     if (ld_in < cols) return HALO_ESHAPE;
     if (ld_q < (axis == HALO_QUANT_ROWS ? cols : rows)) return HALO_ESHAPE;
     if (!aligned16(in) || !aligned16(out_q) || (ld_in * esz) % 16 || ld_q % 16) return HALO_EALIGN;
-    halo_status st = check_block(had_block, cols, kMaxRightBlock);
+    halo_status st = check_right_block(had_block, cols);
     if (st != HALO_OK) return st;
     st = check_block(had_block_left, rows, kMaxLeftBlock);
     if (st != HALO_OK) return st;
@@ -219,7 +239,7 @@ halo_status halo_hadamard_quant_tensor(const void* in, halo_dtype in_dt, int64_t
     // phase 1: rotate, absmax of every row; then the maximum of those
     RowArgs r{};
     r.in = src; r.ld_in = ld_src; r.rows = rows; r.cols = cols;
-    r.log_block = had_block ? ilog2_exact(had_block) : 0;
+    set_right_block(r, had_block);
     r.out = out_q; r.ld_out = ld_q; r.out_scale = row_max; r.amax_only = 1;
     if (launch_row_transform(r, src_kind, OUT_Q8, s) != hipSuccess) return HALO_EHIP;
     if (launch_reduce_max(row_max, rows, tensor_max, s) != hipSuccess) return HALO_EHIP;
@@ -404,7 +424,7 @@ halo_status halo_dequant_unrotate(const int32_t* acc, int64_t ld_acc, int64_t ro
     if (ld_acc < cols || ld_out < cols) return HALO_ESHAPE;
     if (!aligned16(acc) || !aligned16(out) || (ld_acc * 4) % 16 || (ld_out * (out_dt == HALO_BF16 ? 2 : 4)) % 16)
         return HALO_EALIGN;
-    halo_status st = check_block(had_block, cols, kMaxRightBlock);
+    halo_status st = check_right_block(had_block, cols);
     if (st != HALO_OK) return st;
     st = check_block(had_block_left, rows, kMaxLeftBlock);
     if (st != HALO_OK) return st;
@@ -415,7 +435,7 @@ halo_status halo_dequant_unrotate(const int32_t* acc, int64_t ld_acc, int64_t ro
 
     RowArgs r{};
     r.in = acc; r.ld_in = ld_acc; r.rows = rows; r.cols = cols; r.pre_scale = row_scale; r.post_scale = tensor_scale;
-    r.log_block = had_block ? ilog2_exact(had_block) : 0;
+    set_right_block(r, had_block);
     if (had_block_left == 0) {
         r.out = out; r.ld_out = ld_out;
         return from_hip(launch_row_transform(r, IN_I32, out_dt == HALO_BF16 ? OUT_BF16 : OUT_F32, s));
@@ -470,7 +490,7 @@ halo_status halo_linear_fwd(const halo_linear_desc* desc, const void* X, const v
         // X and W get the same treatment: one launch rotates and quantises both
         RowArgs r{};
         r.in = X; r.ld_in = m; r.rows = b; r.cols = m; r.out = Xq; r.ld_out = m; r.out_scale = s_x;
-        r.log_block = hm ? ilog2_exact(hm) : 0;
+        set_right_block(r, hm);
         r.rows2 = n; r.in2 = W; r.out2 = Wq; r.out_scale2 = s_w;
         if (launch_row_transform(r, IN_BF16, OUT_Q8, reinterpret_cast<hipStream_t>(stream)) != hipSuccess) return HALO_EHIP;
         return halo_gemm_i8(Xq, m, Wq, m, 1, b, n, m, s_x, s_w, Y, odt, n, nullptr, 0, stream);
@@ -585,7 +605,7 @@ halo_status halo_linear_bwd(const halo_linear_desc* desc, const void* E, const i
     if (both && level == 1 && !tensor) {
         RowArgs r{};
         r.in = acc; r.ld_in = m; r.rows = b; r.cols = m; r.pre_scale = s_e; r.out = EX; r.ld_out = m;
-        r.log_block = hm ? ilog2_exact(hm) : 0;
+        set_right_block(r, hm);
         r.rows2 = n; r.in2 = acc_g; r.pre_scale2 = s_g; r.out2 = G;
         if (launch_row_transform(r, IN_I32, odt == HALO_BF16 ? OUT_BF16 : OUT_F32, hs) != hipSuccess) return HALO_EHIP;
         return HALO_OK;

@@ -22,6 +22,7 @@ struct RowArgs {
     int64_t ld_out;
     float* out_scale;        // OUT_Q8 only
     int log_block;           // log2 of the Hadamard block, 0 = no rotation
+    int kron_m;              // 0, or 28: the block is 28 * 2^log_block elements, rotated by H_{2^log_block} (x) H_28
     // One scale per tensor (OUT_Q8 only): amax_only writes each row's absmax to out_scale and no codes; given_amax
     // (device scalar) replaces the row's own absmax.  post_scale (IN_I32 only, device scalar) is multiplied in after
     // pre_scale.  All three apply to both matrices of a batched launch.
@@ -44,6 +45,10 @@ struct RowArgs {
 // Largest row length the row kernels accept.
 constexpr int64_t kMaxRowCols = 32768;
 hipError_t launch_row_transform(const RowArgs& a, InKind in, OutKind out, hipStream_t s);
+// Kronecker blocks (kron_m == 28): true if a row of `cols` elements can be rotated in blocks of `block` = 28 * 2^n
+// elements (64 <= 2^n <= 512, block divides cols, cols <= 14336).  launch_row_transform forwards such launches.
+bool row_kron_shape_ok(int64_t cols, int64_t block);
+hipError_t launch_row_kron(const RowArgs& a, InKind in, OutKind out, hipStream_t s);
 
 // ---- left-hand (strided axis) FWHT: all stages of block 2^log_block, ascending, possibly several passes ----
 // in/out may alias when in_kind == out_kind == fp32.  tmp (fp32 [rows x ld_tmp]) is used when more than one

@@ -528,6 +528,7 @@ hipError_t launch_by_seg(const RowArgs& a, hipStream_t s) {
 
 hipError_t launch_row_transform(const RowArgs& a, InKind in, OutKind out, hipStream_t s) {
     if ((a.rows == 0 && a.rows2 == 0) || a.cols == 0) return hipSuccess;
+    if (a.kron_m != 0) return out == OUT_MX6 ? hipErrorInvalidValue : launch_row_kron(a, in, out, s);
     if (a.cols > kMaxRowCols || a.log_block > 12) return hipErrorInvalidValue;
     if (in == IN_BF16 && out == OUT_Q8) return launch_by_seg<IN_BF16, OUT_Q8>(a, s);
     if (in == IN_F32 && out == OUT_Q8) return launch_by_seg<IN_F32, OUT_Q8>(a, s);

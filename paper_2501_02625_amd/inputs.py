@@ -123,10 +123,16 @@ class LayerConfig:
     outlier_frac: float
     backward: bool
     seed: int = 0
+    kronecker: bool = False       # in-feature widths of the form 2^n * 28 get one block of the whole width
 
     def had_block_m(self, m: int) -> int:
-        """Right-hand Hadamard block: largest power of two dividing m (block-diagonal otherwise)."""
-        return m & -m
+        """Right-hand Hadamard block: the largest power of two dividing m, at most 4096 (block-diagonal when that is
+        not m itself); with `kronecker`, the whole of m when m = 2^n * 28 with 64 <= 2^n <= 512."""
+        if self.kronecker and m % 28 == 0:
+            p = m // 28
+            if p & (p - 1) == 0 and 64 <= p <= 512:
+                return m
+        return min(m & -m, 4096)
 
     def had_block_b(self) -> int:
         """Left-hand Hadamard block over tokens: largest power of two dividing b."""
@@ -160,6 +166,9 @@ CONFIGS: Dict[str, LayerConfig] = {
     # MXFP6 variant: 8192 x 4096 . 4096 x 4096, FP6 E3M2 with an E8M0 scale per 32 along K after the rotation, forward product.
     "c5": LayerConfig("c5", 8192, (LinearShape("proj", 4096, 4096),), level=1,
                       outlier_frac=0.001, backward=False, seed=5),
+    # The shape of c3 with the paper's Kronecker rotation H_512 (x) H_28 over K = 14336 in place of the block-diagonal one.
+    "c6": LayerConfig("c6", 4096, (LinearShape("down", 4096, 14336),), level=2,
+                      outlier_frac=0.001, backward=True, seed=6, kronecker=True),
 }
 
 

@@ -72,6 +72,24 @@ def test_hadamard_quant_argument_errors(lib):
     assert good
 
 
+def test_kronecker_block_argument_errors(lib):
+    """Blocks of the form 28 * 2^n: the Walsh-Hadamard factor must lie in [64, 512], the block must divide the row and
+    the row may hold at most 14336 elements; the microscaling quantiser takes power-of-two blocks only."""
+    f = lib.halo_hadamard_quant
+    A, Q, S = _p(0x1000), _p(0x2000), _p(0x3000)
+    assert f(A, 0, 64, 896, 896, 0, 896, 0, None, Q, 896, S, None, 0, None) == binding.HALO_EUNSUPPORTED       # 32 * 28
+    assert f(A, 0, 64, 28672, 28672, 0, 28672, 0, None, Q, 28672, S, None, 0, None) == binding.HALO_EUNSUPPORTED
+    assert f(A, 0, 64, 28672, 28672, 0, 14336, 0, None, Q, 28672, S, None, 0, None) == binding.HALO_EUNSUPPORTED
+    assert f(A, 0, 64, 2048, 2048, 0, 1792, 0, None, Q, 2048, S, None, 0, None) == binding.HALO_ESHAPE         # does not divide
+    assert f(A, 0, 64, 5376, 5376, 0, 5376, 0, None, Q, 5376, S, None, 0, None) == binding.HALO_ESHAPE         # 3 * 64 * 28
+    u = lib.halo_dequant_unrotate
+    assert u(A, 2048, 16, 2048, None, None, 1792, 0, Q, 1, 2048, None, 0, None) == binding.HALO_ESHAPE
+    assert lib.halo_mx6_quant(A, 64, 1792, 1792, 1792, Q, 1344, S, 64, None) == binding.HALO_ESHAPE
+    d = binding.make_desc(64, 28672, 128, 1, had_block_m=14336)
+    P = _p(0x1000)
+    assert lib.halo_linear_fwd(ctypes.byref(d), P, P, P, P, P, P, P, None, 0, None) == binding.HALO_EUNSUPPORTED
+
+
 def test_quant_dual_argument_errors(lib):
     f = lib.halo_quant_dual
     A, Q, S, T, U, W = _p(0x1000), _p(0x2000), _p(0x3000), _p(0x4000), _p(0x5000), _p(0x6000)
@@ -223,3 +241,4 @@ def test_inputs_are_deterministic_and_shaped():
     assert np.max(np.abs(E)) > 8 * np.median(np.abs(E))     # heavy tails
     assert inputs.CONFIGS["c2"].gemm_ops() == 6 * 2048 * 4096 * 4096
     assert inputs.CONFIGS["c3"].had_block_m(14336) == 2048
+    assert inputs.CONFIGS["c6"].had_block_m(14336) == 14336 and inputs.CONFIGS["c6"].had_block_m(4096) == 4096
