@@ -243,8 +243,10 @@ halo_status halo_gemm_mx6(const uint8_t* A, int64_t lda, const uint8_t* scales_a
  * halo_dequant_unrotate: the tail of both backward products.   (Table "HALO levels": the trailing H^T
  * of  (E_Y)_Q (WH)_Q H^T  and  (E_Y^T)_Q (XH)_Q H^T,  and the leading H^T of level 2.)
  *
- *   T[r,k] = (float(acc[r,k]) * row_scale[r]) * tensor_scale[0];   T <- T (I (x) H_had_block)   (right-hand, if had_block)
- *   T <- (I (x) H_had_block_left)^T T          (left-hand, if had_block_left);   out = T rounded to out_dt.
+ *   T[r,k] = (float(acc[r,k]) * row_scale[r]) * tensor_scale[0];
+ *   T <- (I (x) H_had_block_left)^T T          (left-hand, if had_block_left: the table does not bracket the two
+ *                                               un-rotations; the left-hand one is taken first);
+ *   T <- T (I (x) H_had_block)                 (right-hand, if had_block);   out = T rounded to out_dt.
  *
  *   acc int32 [rows x cols] ld_acc; row_scale fp32 [rows] or NULL; tensor_scale: device pointer to ONE fp32 or NULL
  *   (the saved operand's scale in the one-scale-per-tensor mode); out bf16/fp32 [rows x cols] ld_out.

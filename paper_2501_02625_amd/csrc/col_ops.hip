@@ -29,7 +29,7 @@ __device__ __forceinline__ uint32_t f32_to_bf16_rne(float f) {
 template <int LOGR, int CPL, int IN, int OUT>
 __global__ void __launch_bounds__(256)
 col_fwht_kernel(const void* in, int64_t ld_in, void* out, int64_t ld_out, int64_t rows, int64_t cols,
-                int p, float c_final, int64_t col_tiles) {
+                int p, float c_final, int64_t col_tiles, const float* row_scale, const float* post_scale) {
     constexpr int R = 1 << LOGR;
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
@@ -60,6 +60,25 @@ col_fwht_kernel(const void* in, int64_t ld_in, void* out, int64_t ld_out, int64_
                 }
             } else {
                 v[t][0] = __uint_as_float((uint32_t)src[0] << 16);
+            }
+        } else if constexpr (IN == IN_I32) {
+            // accumulators of a product: (float(acc) * scale of the row) * tensor-wide scale, as the row kernel does
+            const int32_t* src = reinterpret_cast<const int32_t*>(in) + r * ld_in + col;
+            const float rs = row_scale ? row_scale[r] : 1.0f;
+            if constexpr (CPL == 2) {
+                if (pair_ok) {
+                    const int2 w = *reinterpret_cast<const int2*>(src);
+                    v[t][0] = (float)w.x * rs; v[t][1] = (float)w.y * rs;
+                } else {
+                    v[t][0] = (float)src[0] * rs; v[t][1] = 0.0f;
+                }
+            } else {
+                v[t][0] = (float)src[0] * rs;
+            }
+            if (post_scale) {
+                const float post = *post_scale;
+#pragma unroll
+                for (int c = 0; c < CPL; ++c) v[t][c] *= post;
             }
         } else {
             const float* src = reinterpret_cast<const float*>(in) + r * ld_in + col;
@@ -124,28 +143,29 @@ col_fwht_kernel(const void* in, int64_t ld_in, void* out, int64_t ld_out, int64_
 
 template <int LOGR, int CPL, int IN, int OUT>
 hipError_t launch_pass(const void* in, int64_t ld_in, void* out, int64_t ld_out, int64_t rows, int64_t cols,
-                       int p, float c_final, hipStream_t s) {
+                       int p, float c_final, hipStream_t s, const float* row_scale, const float* post_scale) {
     const int64_t col_tiles = (cols + 256 * CPL - 1) / (256 * CPL);
     const int64_t groups = rows >> LOGR;
     const int64_t blocks = col_tiles * groups;
     if (blocks <= 0 || blocks > 0x7FFFFFFF) return hipErrorInvalidValue;
     hipLaunchKernelGGL((col_fwht_kernel<LOGR, CPL, IN, OUT>), dim3((unsigned)blocks), dim3(256), 0, s, in, ld_in,
-                       out, ld_out, rows, cols, p, c_final, col_tiles);
+                       out, ld_out, rows, cols, p, c_final, col_tiles, row_scale, post_scale);
     return hipGetLastError();
 }
 
 template <int IN, int OUT>
 hipError_t launch_pass_by_logr(int logr, const void* in, int64_t ld_in, void* out, int64_t ld_out, int64_t rows,
-                               int64_t cols, int p, float c_final, hipStream_t s) {
+                               int64_t cols, int p, float c_final, hipStream_t s, const float* row_scale = nullptr,
+                               const float* post_scale = nullptr) {
     switch (logr) {
-        case 1: return launch_pass<1, 2, IN, OUT>(in, ld_in, out, ld_out, rows, cols, p, c_final, s);
-        case 2: return launch_pass<2, 2, IN, OUT>(in, ld_in, out, ld_out, rows, cols, p, c_final, s);
-        case 3: return launch_pass<3, 2, IN, OUT>(in, ld_in, out, ld_out, rows, cols, p, c_final, s);
-        case 4: return launch_pass<4, 2, IN, OUT>(in, ld_in, out, ld_out, rows, cols, p, c_final, s);
-        case 5: return launch_pass<5, 2, IN, OUT>(in, ld_in, out, ld_out, rows, cols, p, c_final, s);
-        case 6: return launch_pass<6, 2, IN, OUT>(in, ld_in, out, ld_out, rows, cols, p, c_final, s);
+        case 1: return launch_pass<1, 2, IN, OUT>(in, ld_in, out, ld_out, rows, cols, p, c_final, s, row_scale, post_scale);
+        case 2: return launch_pass<2, 2, IN, OUT>(in, ld_in, out, ld_out, rows, cols, p, c_final, s, row_scale, post_scale);
+        case 3: return launch_pass<3, 2, IN, OUT>(in, ld_in, out, ld_out, rows, cols, p, c_final, s, row_scale, post_scale);
+        case 4: return launch_pass<4, 2, IN, OUT>(in, ld_in, out, ld_out, rows, cols, p, c_final, s, row_scale, post_scale);
+        case 5: return launch_pass<5, 2, IN, OUT>(in, ld_in, out, ld_out, rows, cols, p, c_final, s, row_scale, post_scale);
+        case 6: return launch_pass<6, 2, IN, OUT>(in, ld_in, out, ld_out, rows, cols, p, c_final, s, row_scale, post_scale);
         case 7:
-            if constexpr (IN == IN_F32) return launch_pass<7, 1, IN, OUT>(in, ld_in, out, ld_out, rows, cols, p, c_final, s);
+            if constexpr (IN == IN_F32) return launch_pass<7, 1, IN, OUT>(in, ld_in, out, ld_out, rows, cols, p, c_final, s, row_scale, post_scale);
             return hipErrorInvalidValue;
         default: return hipErrorInvalidValue;
     }
@@ -528,16 +548,18 @@ dual_quant_kernel(const uint16_t* __restrict__ in, int64_t ld_in, int64_t rows, 
 
 hipError_t launch_col_fwht(const ColFwhtArgs& a, hipStream_t s) {
     if (a.rows == 0 || a.cols == 0 || a.log_block == 0) return hipSuccess;
-    // split the log_block stages into passes of at most 6 (a final 7 is allowed for fp32 input)
-    int sizes[8], np = 0, left = a.log_block;
+    if (a.first_stage < 0 || a.first_stage > a.log_block) return hipErrorInvalidValue;
+    // split the remaining stages into passes of at most 6 (a final 7 is allowed for fp32 input)
+    int sizes[8], np = 0, left = a.log_block - a.first_stage;
+    if (left == 0) return (a.in == a.out && a.skip_norm) ? hipSuccess : hipErrorInvalidValue;   // nothing left to do in place
     while (left > 0) {
         int q = left <= 6 ? left : (left == 7 && np > 0 ? 7 : 6);
         sizes[np++] = q;
         left -= q;
         if (np >= 8) return hipErrorInvalidValue;
     }
-    const float c = (float)(1.0 / sqrt((double)(int64_t(1) << a.log_block)));
-    int p = 0;
+    const float c = a.skip_norm ? 1.0f : (float)(1.0 / sqrt((double)(int64_t(1) << a.log_block)));
+    int p = a.first_stage;
     for (int i = 0; i < np; ++i) {
         const bool first = i == 0, last = i == np - 1;
         const void* src = first ? a.in : (const void*)a.tmp;
@@ -554,6 +576,9 @@ hipError_t launch_col_fwht(const ColFwhtArgs& a, hipStream_t s) {
             e = launch_pass_by_logr<IN_F32, OUT_F32>(sizes[i], src, ld_src, dst, ld_dst, a.rows, a.cols, p, cf, s);
         else if (ik == IN_F32 && ok == OUT_BF16)
             e = launch_pass_by_logr<IN_F32, OUT_BF16>(sizes[i], src, ld_src, dst, ld_dst, a.rows, a.cols, p, cf, s);
+        else if (ik == IN_I32 && ok == OUT_F32)
+            e = launch_pass_by_logr<IN_I32, OUT_F32>(sizes[i], src, ld_src, dst, ld_dst, a.rows, a.cols, p, cf, s, a.row_scale,
+                                                     a.post_scale);
         else
             e = hipErrorInvalidValue;
         if (e != hipSuccess) return e;

@@ -440,13 +440,16 @@ halo_status halo_dequant_unrotate(const int32_t* acc, int64_t ld_acc, int64_t ro
         r.out = out; r.ld_out = ld_out;
         return from_hip(launch_row_transform(r, IN_I32, out_dt == HALO_BF16 ? OUT_BF16 : OUT_F32, s));
     }
+    // Left-hand un-rotation first: strided passes from the accumulators into the fp32 scratch (butterflies only), then
+    // the row kernel multiplies by 1/sqrt(left block), un-rotates along the rows and converts.
     float* tmp = reinterpret_cast<float*>(workspace);
-    r.out = tmp; r.ld_out = cols;
-    hipError_t e = launch_row_transform(r, IN_I32, OUT_F32, s);
-    if (e != hipSuccess) return HALO_EHIP;
-    ColFwhtArgs c{tmp, IN_F32, cols, out, out_dt == HALO_BF16 ? OUT_BF16 : OUT_F32, ld_out, tmp, cols, rows, cols,
-                  ilog2_exact(had_block_left)};
-    return from_hip(launch_col_fwht(c, s));
+    ColFwhtArgs c{acc, IN_I32, ld_acc, tmp, OUT_F32, cols, tmp, cols, rows, cols, ilog2_exact(had_block_left)};
+    c.row_scale = row_scale; c.post_scale = tensor_scale; c.skip_norm = 1;
+    if (launch_col_fwht(c, s) != hipSuccess) return HALO_EHIP;
+    r.in = tmp; r.ld_in = cols; r.pre_scale = nullptr; r.post_scale = nullptr;
+    r.in_mul = (float)(1.0 / sqrt((double)had_block_left));
+    r.out = out; r.ld_out = ld_out;
+    return from_hip(launch_row_transform(r, IN_F32, out_dt == HALO_BF16 ? OUT_BF16 : OUT_F32, s));
 }
 
 // ------------------------------------------------------------------------------------------------

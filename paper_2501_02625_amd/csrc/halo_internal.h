@@ -23,6 +23,7 @@ struct RowArgs {
     float* out_scale;        // OUT_Q8 only
     int log_block;           // log2 of the Hadamard block, 0 = no rotation
     int kron_m;              // 0, or 28: the block is 28 * 2^log_block elements, rotated by H_{2^log_block} (x) H_28
+    float in_mul;            // IN_F32 only: every element is multiplied by this once when it is loaded; 0 = no multiply
     // One scale per tensor (OUT_Q8 only): amax_only writes each row's absmax to out_scale and no codes; given_amax
     // (device scalar) replaces the row's own absmax.  post_scale (IN_I32 only, device scalar) is multiplied in after
     // pre_scale.  All three apply to both matrices of a batched launch.
@@ -64,6 +65,13 @@ struct ColFwhtArgs {
     int64_t ld_tmp;
     int64_t rows, cols;
     int log_block;
+    // IN_I32 input (accumulators of a product): element (r, k) enters as (float(in[r,k]) * row_scale[r]) * post_scale[0]
+    // (either pointer may be null).  first_stage: the strides below 2^first_stage have been applied already.  skip_norm:
+    // leave the 1/sqrt(block) multiply to the caller.
+    const float* row_scale;
+    const float* post_scale;
+    int first_stage;
+    int skip_norm;
 };
 hipError_t launch_col_fwht(const ColFwhtArgs& a, hipStream_t s);
 
@@ -122,6 +130,11 @@ struct GemmArgs {
     int32_t* acc_out;
     int64_t ld_acc;
     int config;              // halo_gemm_config: -1 = chosen by shape
+    // left_stages == 8 (256-row tiles only, C fp32, M a multiple of 256): the epilogue scales the accumulators,
+    // (float(acc) * row_scale[row]) * post_scale[0], and then runs the eight lowest strides (1 .. 128 rows) of a left-hand
+    // Walsh-Hadamard rotation down each column of the tile, unnormalised, before it stores C.
+    int left_stages;
+    const float* post_scale;
 };
 hipError_t launch_gemm_i8(const GemmArgs& a, hipStream_t s);
 hipError_t launch_gemm_i8_pair(const GemmArgs& a1, const GemmArgs& a2, hipStream_t s);

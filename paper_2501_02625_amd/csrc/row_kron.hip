@@ -132,6 +132,10 @@ row_kron28_kernel(RowArgs a, float c_norm, unsigned blocks1) {
             const float4 w = src[q];
             x[4 * q + 0] = w.x; x[4 * q + 1] = w.y; x[4 * q + 2] = w.z; x[4 * q + 3] = w.w;
         }
+        if (a.in_mul != 0.0f) {
+#pragma unroll
+            for (int j = 0; j < kM; ++j) x[j] *= a.in_mul;
+        }
     } else {
         const float pre = a.pre_scale ? a.pre_scale[row] : 1.0f;
         const int4* src = reinterpret_cast<const int4*>(reinterpret_cast<const int32_t*>(a.in) + row * a.ld_in + k0);
@@ -274,6 +278,8 @@ hipError_t launch_row_kron(const RowArgs& a, InKind in, OutKind out, hipStream_t
     if (in == IN_F32 && out == OUT_Q8) return launch_kind<IN_F32, OUT_Q8>(a, s);
     if (in == IN_I32 && out == OUT_BF16) return launch_kind<IN_I32, OUT_BF16>(a, s);
     if (in == IN_I32 && out == OUT_F32) return launch_kind<IN_I32, OUT_F32>(a, s);
+    if (in == IN_F32 && out == OUT_BF16) return launch_kind<IN_F32, OUT_BF16>(a, s);
+    if (in == IN_F32 && out == OUT_F32) return launch_kind<IN_F32, OUT_F32>(a, s);
     return hipErrorInvalidValue;
 }
 

@@ -203,6 +203,12 @@ __device__ __forceinline__ float row_phase1(const RowArgs& a, const RowCtx& x, f
         }
     }
 
+    if constexpr (IN == IN_F32) {
+        if (a.in_mul != 0.0f) {      // e.g. the 1/sqrt(block) of a left-hand rotation whose butterflies ran before
+#pragma unroll
+            for (int r = 0; r < VPL; ++r) v[r] *= a.in_mul;
+        }
+    }
     if constexpr (IN == IN_I32) {
         if (a.post_scale) {          // one more (tensor-wide) scale, applied after the per-row one
             const float post = *a.post_scale;
@@ -534,6 +540,8 @@ hipError_t launch_row_transform(const RowArgs& a, InKind in, OutKind out, hipStr
     if (in == IN_F32 && out == OUT_Q8) return launch_by_seg<IN_F32, OUT_Q8>(a, s);
     if (in == IN_I32 && out == OUT_BF16) return launch_by_seg<IN_I32, OUT_BF16>(a, s);
     if (in == IN_I32 && out == OUT_F32) return launch_by_seg<IN_I32, OUT_F32>(a, s);
+    if (in == IN_F32 && out == OUT_BF16) return launch_by_seg<IN_F32, OUT_BF16>(a, s);
+    if (in == IN_F32 && out == OUT_F32) return launch_by_seg<IN_F32, OUT_F32>(a, s);
     if (in == IN_BF16 && out == OUT_MX6) return a.cols % 32 == 0 ? launch_by_seg<IN_BF16, OUT_MX6>(a, s) : hipErrorInvalidValue;
     return hipErrorInvalidValue;
 }

@@ -172,8 +172,8 @@ def test_dequant_unrotate(rows, cols, hb, hbl, odt):
     scale = (np.abs(rng.standard_normal(rows)) * 1e-6 + 1e-8).astype(np.float32)
     out = binding.halo_dequant_unrotate(gu.to_dev(acc), gu.to_dev(scale), had_block=hb, had_block_left=hbl, out_dtype=odt)
     T = orc.dequantize(acc, scale)
+    T = orc.fwht(T, hbl, 0) if hbl else T          # the left-hand un-rotation comes first (as in the oracle's level 2)
     T = orc.fwht(T, hb, 1)
-    T = orc.fwht(T, hbl, 0) if hbl else T
     if odt == torch.float32:
         gu.assert_f32_identical(out, T, "unrotated fp32 (same stage order => same bits)")
     else:
