@@ -66,6 +66,7 @@ template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, bool TRANSB, int NS,
 struct GemmCfg {
     static constexpr bool IS_TR = TR;
     static constexpr int BN_ = BN;
+    static constexpr int WAVES_M_ = WAVES_M, WAVES_N_ = WAVES_N;
     static constexpr int NT = 64 * WAVES_M * WAVES_N;
     // tile-rows per group of the workgroup->tile map (4 measured best of 2/4/8/16 on the Llama-shaped products)
     static constexpr int GROUP_M = 4;
@@ -351,9 +352,131 @@ __device__ __forceinline__ void epilogue(const GemmArgs& a, int64_t m0, int64_t 
     }
 }
 
+// Epilogue of a product whose output is then un-rotated on the left (level 2, E_X = H^T ( ... )): the accumulators are
+// scaled, (float(acc) * row_scale[row]) * post_scale, and the eight lowest strides of the left-hand Walsh-Hadamard
+// rotation run on the 256 rows of the tile before anything is stored, in ascending order and with every add and
+// subtract a separately rounded fp32 operation, exactly as a pass over memory would do them.  Row index inside the
+// tile = [wave_m | tile i (2 bits) | r >> 2 (2 bits) | lane half | r & 3 (2 bits)], so strides 1, 2 pair registers,
+// stride 4 pairs the two halves of the wavefront, strides 8 .. 64 pair registers again, and stride 128 pairs this
+// wavefront with the one holding the other 128 rows of the same columns: that last stage is folded into the slab
+// staging of the store (each wavefront reads its own slab and its partner's).  The columns are independent, so one
+// 32-column tile of the wavefront is taken through all of this at a time (64 live values per lane).  No normalisation:
+// the 1/sqrt(block) of the rotation is applied after its last stride, by whoever runs it.
+template <class Cfg>
+__device__ __forceinline__ void epilogue_left8(const GemmArgs& a, int64_t m0, int64_t n0, int wave, int wave_m, int wave_n,
+                                               int lane, const v16i (&acc)[Cfg::TM][Cfg::TN], unsigned char* smem) {
+    static_assert(Cfg::TM == 4 && Cfg::WAVES_M_ == 2, "256-row tiles, two wavefronts down the rows");
+    constexpr int WN = Cfg::WN, TM = Cfg::TM, TN = Cfg::TN;
+    constexpr int PITCH = 32 + 8;          // dwords per row of a staged 32 x 32 slab: conflict-free writes, 16-byte rows
+    constexpr int SLAB = 32 * PITCH;       // one slab; a wavefront's region holds two (64 rows of one column tile)
+    static_assert(1024 + 8 * 2 * SLAB * 4 <= Cfg::LDS_BYTES, "row scales and staging regions fit the operand stages' LDS");
+    const int lrow = lane & 31, half = lane >> 5;
+    float* s_scale = reinterpret_cast<float*>(smem);
+    float* region = reinterpret_cast<float*>(smem + 1024) + wave * 2 * SLAB;
+    const float* partner = reinterpret_cast<const float*>(smem + 1024) + (wave ^ Cfg::WAVES_N_) * 2 * SLAB;
+    __syncthreads();                       // every wavefront is done with the operand stages
+    const int tid = wave * 64 + lane;
+    if (tid < 256) s_scale[tid] = a.row_scale ? a.row_scale[m0 + tid] : 1.0f;      // M is a multiple of 256
+    __syncthreads();
+    const float post = a.post_scale ? *a.post_scale : 1.0f;                          // x * 1.0f is x
+    const float sgn = half ? -1.0f : 1.0f;                   // lower half: a + b;  upper half: a - b = partner - own
+    const float sgn_w = wave_m ? -1.0f : 1.0f;               // the same for the two wavefronts of stride 128
+    const int addr = (lane ^ 32) << 2;
+    const int cc = (lane & 7) * 4;                           // read-back: 8 lanes per 32-column row, 8 rows per pass
+
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        float f[TM][16];
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const float rs = s_scale[wave_m * 128 + i * 32 + 8 * (r >> 2) + 4 * half + (r & 3)];
+                f[i][r] = ((float)acc[i][j][r] * rs) * post;
+            }
+        // strides 1, 2, (4), 8, 16: bits 0, 1, 2, 3 of r; stride 4 across the lane halves in between
+#pragma unroll
+        for (int bit = 0; bit < 4; ++bit) {
+            if (bit == 2) {
+#pragma unroll
+                for (int i = 0; i < TM; ++i) {
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const float p = __int_as_float(__builtin_amdgcn_ds_bpermute(addr, __float_as_int(f[i][r])));
+                        f[i][r] = __builtin_fmaf(f[i][r], sgn, p);             // the product is exact: one rounded add/sub
+                    }
+                    __builtin_amdgcn_sched_barrier(0);       // sixteen exchanges in flight at a time, not sixty-four
+                }
+            }
+            const int h = 1 << bit;
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    if ((r & h) == 0) {
+                        const float x = f[i][r], y = f[i][r | h];
+                        f[i][r] = x + y;
+                        f[i][r | h] = x - y;
+                    }
+        }
+        // strides 32, 64: the four 32-row tiles of the wavefront
+#pragma unroll
+        for (int bit = 0; bit < 2; ++bit) {
+            const int h = 1 << bit;
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+                if ((i & h) == 0) {
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const float x = f[i][r], y = f[i | h][r];
+                        f[i][r] = x + y;
+                        f[i | h][r] = x - y;
+                    }
+                }
+        }
+        // stride 128 and the store, 64 rows (two slabs) at a time: the slabs go to the wavefront's region, then every
+        // lane combines four consecutive columns of its own and its partner's slabs
+        const int64_t col = n0 + wave_n * WN + j * 32 + cc;
+        const bool col_any = col < a.N, col_all = col + 4 <= a.N;
+#pragma unroll
+        for (int hs = 0; hs < TM / 2; ++hs) {
+            if (j > 0 || hs > 0) __syncthreads();      // the previous slabs have been read by both wavefronts
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    region[i * SLAB + (8 * (r / 4) + 4 * half + (r % 4)) * PITCH + lrow] = f[2 * hs + i][r];
+            __syncthreads();                           // the partner's slabs are written too
+#pragma unroll
+            for (int p = 0; p < 8; ++p) {
+                const int rr = p * 8 + (lane >> 3);            // row inside these 64
+                const int off = (rr >> 5) * SLAB + (rr & 31) * PITCH + cc;
+                const float4 own = *reinterpret_cast<const float4*>(region + off);
+                const float4 oth = *reinterpret_cast<const float4*>(partner + off);
+                // wave_m == 0: own + other;  wave_m == 1: other - own (the product own * -1 is exact)
+                const float v[4] = {__builtin_fmaf(own.x, sgn_w, oth.x), __builtin_fmaf(own.y, sgn_w, oth.y),
+                                    __builtin_fmaf(own.z, sgn_w, oth.z), __builtin_fmaf(own.w, sgn_w, oth.w)};
+                if (!col_any) continue;
+                const int64_t row = m0 + wave_m * Cfg::WM + hs * 64 + rr;
+                float* dst = reinterpret_cast<float*>(a.C) + row * a.ldc + col;
+                if (col_all) {
+                    *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[2], v[3]);
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (col + e < a.N) dst[e] = v[e];
+                }
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);     // finish this column tile before the next one starts
+    }
+}
+
 // ------------------------------------------------------------------------------------------------ dma main loop
 // Both operands go through the DMA ring.  K must be a multiple of BK (the DMA cannot zero-fill a K tail).
-template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, bool TRANSB, int NS>
+// LEFT: this instance also carries the epilogue that runs the low strides of a left-hand rotation (its own instance, so
+// that the register spills of that epilogue stay out of the kernels that never take it).
+template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, bool TRANSB, int NS, bool LEFT = false>
 __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N)
 gemm_i8_dma_kernel(GemmArgs a, int tiles_m, int tiles_n, GemmArgs a2, int tiles_m2, int tiles_n2, unsigned blocks1) {
     using Cfg = GemmCfg<BM, BN, BK, WAVES_M, WAVES_N, TRANSB, NS, !TRANSB>;
@@ -466,6 +589,12 @@ gemm_i8_dma_kernel(GemmArgs a, int tiles_m, int tiles_n, GemmArgs a2, int tiles_
             }
         }
         asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+    }
+    if constexpr (LEFT) {
+        if (a.left_stages != 0) {          // uniform over the workgroup
+            epilogue_left8<Cfg>(a, m0, n0, wave, wave_m, wave_n, lane, acc, smem);
+            return;
+        }
     }
     epilogue<Cfg>(a, m0, n0, wave, wave_m, wave_n, lane, acc, smem);
 }
@@ -641,15 +770,26 @@ hipError_t raise_lds_limit(Kern kern, int lds_bytes, std::once_flag* once, hipEr
     return *result;
 }
 
-template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, bool TRANSB, int NS>
+template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, bool TRANSB, int NS, bool LEFT = false>
 hipError_t launch_dma(const GemmArgs& a, hipStream_t s, const GemmArgs* a2 = nullptr) {
     using Cfg = GemmCfg<BM, BN, BK, WAVES_M, WAVES_N, TRANSB, NS, !TRANSB>;
+    const bool wants_left = a.left_stages != 0 || (a2 && a2->left_stages != 0);
+    if constexpr (!LEFT && BM == 256 && WAVES_M == 2 && !TRANSB) {
+        if (wants_left) return launch_dma<BM, BN, BK, WAVES_M, WAVES_N, TRANSB, NS, true>(a, s, a2);
+    }
+    if (wants_left && !LEFT) return hipErrorInvalidValue;
     static std::once_flag once;
     static hipError_t attr_result = hipSuccess;
-    auto kern = gemm_i8_dma_kernel<BM, BN, BK, WAVES_M, WAVES_N, TRANSB, NS>;
+    auto kern = gemm_i8_dma_kernel<BM, BN, BK, WAVES_M, WAVES_N, TRANSB, NS, LEFT>;
     hipError_t e = raise_lds_limit(kern, Cfg::LDS_BYTES, &once, &attr_result);
     if (e != hipSuccess) return e;
     if (a.K % BK != 0 || (a2 && a2->K % BK != 0)) return hipErrorInvalidValue;
+    // the epilogue that runs the low strides of a left-hand rotation: 256-row tiles that lie inside the matrix, fp32 out
+    auto left_ok = [](const GemmArgs& g) {
+        if (g.left_stages == 0) return true;
+        return g.left_stages == 8 && g.M % 256 == 0 && g.C && g.c_is_f32 && !g.acc_out && !g.col_scale && g.K > 0;
+    };
+    if (!left_ok(a) || (a2 && !left_ok(*a2))) return hipErrorInvalidValue;
     const int tiles_m = (int)((a.M + BM - 1) / BM), tiles_n = (int)((a.N + BN - 1) / BN);
     const unsigned blocks1 = (unsigned)(tiles_m * tiles_n);
     int tiles_m2 = 0, tiles_n2 = 0;
@@ -667,6 +807,7 @@ hipError_t launch_staged(const GemmArgs& a, hipStream_t s) {
     using Cfg = GemmCfg<128, 128, 64, 2, 2, TRANSB, 2>;
     static std::once_flag once;
     static hipError_t attr_result = hipSuccess;
+    if (a.left_stages != 0) return hipErrorInvalidValue;
     auto kern = gemm_i8_staged_kernel<128, 128, 64, 2, 2, TRANSB>;
     hipError_t e = raise_lds_limit(kern, Cfg::LDS_BYTES, &once, &attr_result);
     if (e != hipSuccess) return e;

@@ -107,6 +107,25 @@ BwdWorkspace bwd_layout(const halo_linear_desc* d) {
     return w;
 }
 
+// Level 2: the low eight strides of the left-hand un-rotation of E_X can run in the epilogue of the E product when the
+// left block covers whole 256-row tiles and the product can take the 256 x 256 configuration (K = n in 64-byte steps).
+inline bool left_in_epilogue(int64_t b, int64_t n, int32_t hb) { return hb >= 256 && b % 256 == 0 && n % 64 == 0; }
+
+// The rest of that un-rotation: t [b x m] fp32 holds the product after the eight low left-hand strides.  Remaining
+// strides in place, then the row kernel (1/sqrt(left block), right-hand un-rotation, conversion).
+hipError_t finish_left_unrotation(float* t, int64_t b, int64_t m, int32_t hb, int32_t hm, void* out, halo_dtype odt,
+                                  hipStream_t s) {
+    ColFwhtArgs c{t, IN_F32, m, t, OUT_F32, m, t, m, b, m, ilog2_exact(hb)};
+    c.first_stage = 8; c.skip_norm = 1;
+    hipError_t e = launch_col_fwht(c, s);
+    if (e != hipSuccess) return e;
+    RowArgs r{};
+    r.in = t; r.ld_in = m; r.rows = b; r.cols = m; r.out = out; r.ld_out = m;
+    r.in_mul = (float)(1.0 / sqrt((double)hb));
+    set_right_block(r, hm);
+    return launch_row_transform(r, IN_F32, odt == HALO_BF16 ? OUT_BF16 : OUT_F32, s);
+}
+
 }  // namespace
 
 extern "C" {
@@ -556,11 +575,19 @@ halo_status halo_linear_bwd(const halo_linear_desc* desc, const void* E, const i
             }
             st = halo_hadamard_quant_tensor(src, src_dt, b, n, n, HALO_QUANT_ROWS, 0, 0, Eq, n, s_e, tq, tq_bytes, stream);
             if (st != HALO_OK) return st;
-            GemmArgs gx{Eq, n, Wq, m, 0, b, m, n, nullptr, nullptr, nullptr, 0, m, acc, m, HALO_GEMM_AUTO};
-            if (launch_gemm_i8(gx, hs) != hipSuccess) return HALO_EHIP;
-            st = halo_dequant_unrotate(acc, m, b, m, s_e, s_w, level >= 1 ? hm : 0, level >= 2 ? hb : 0, EX, odt, m, f32,
-                                       level >= 2 ? round256((size_t)b * m * 4) : 0, stream);
-            if (st != HALO_OK) return st;
+            if (level >= 2 && left_in_epilogue(b, n, hb)) {
+                GemmArgs gx{Eq, n, Wq, m, 0, b, m, n, s_e, nullptr, acc, 1, m, nullptr, 0, HALO_GEMM_256x256x64};
+                gx.left_stages = 8; gx.post_scale = s_w;
+                if (launch_gemm_i8(gx, hs) != hipSuccess) return HALO_EHIP;
+                if (finish_left_unrotation(reinterpret_cast<float*>(acc), b, m, hb, hm, EX, odt, hs) != hipSuccess)
+                    return HALO_EHIP;
+            } else {
+                GemmArgs gx{Eq, n, Wq, m, 0, b, m, n, nullptr, nullptr, nullptr, 0, m, acc, m, HALO_GEMM_AUTO};
+                if (launch_gemm_i8(gx, hs) != hipSuccess) return HALO_EHIP;
+                st = halo_dequant_unrotate(acc, m, b, m, s_e, s_w, level >= 1 ? hm : 0, level >= 2 ? hb : 0, EX, odt, m, f32,
+                                           level >= 2 ? round256((size_t)b * m * 4) : 0, stream);
+                if (st != HALO_OK) return st;
+            }
         }
         if (G) {
             st = halo_hadamard_quant_tensor(E, HALO_BF16, b, n, n, HALO_QUANT_COLS_T, 0, 0, EqT, b, s_g, tq, tq_bytes, stream);
@@ -597,6 +624,14 @@ halo_status halo_linear_bwd(const halo_linear_desc* desc, const void* E, const i
                 odt == HALO_F32 ? 1 : 0, m, level == 0 ? nullptr : acc, m, HALO_GEMM_AUTO};
     GemmArgs gg{EqT, b, Xq, m, 0, n, m, b, level == 0 ? s_g : nullptr, nullptr, level == 0 ? G : nullptr,
                 odt == HALO_F32 ? 1 : 0, m, level == 0 ? nullptr : acc_g, m, HALO_GEMM_AUTO};
+    // Level 2: the E product scales its accumulators and runs the low strides of the left-hand un-rotation in its
+    // epilogue, and leaves fp32 where the int32 accumulators would go (same size).
+    const bool left_fused = EX && level >= 2 && left_in_epilogue(b, n, hb);
+    if (left_fused) {
+        gx.row_scale = s_e; gx.C = acc; gx.c_is_f32 = 1; gx.ldc = m; gx.acc_out = nullptr; gx.left_stages = 8;
+        gx.config = HALO_GEMM_256x256x64;
+        gg.config = HALO_GEMM_256x256x64;
+    }
     hipError_t he = hipSuccess;
     if (both) he = launch_gemm_i8_pair(gx, gg, hs);
     else if (EX) he = launch_gemm_i8(gx, hs);
@@ -613,7 +648,9 @@ halo_status halo_linear_bwd(const halo_linear_desc* desc, const void* E, const i
         if (launch_row_transform(r, IN_I32, odt == HALO_BF16 ? OUT_BF16 : OUT_F32, hs) != hipSuccess) return HALO_EHIP;
         return HALO_OK;
     }
-    if (EX) {
+    if (left_fused) {
+        if (finish_left_unrotation(reinterpret_cast<float*>(acc), b, m, hb, hm, EX, odt, hs) != hipSuccess) return HALO_EHIP;
+    } else if (EX) {
         st = halo_dequant_unrotate(acc, m, b, m, s_e, nullptr, hm, level >= 2 ? hb : 0, EX, odt, m, f32,
                                    level >= 2 ? round256((size_t)b * m * 4) : 0, stream);
         if (st != HALO_OK) return st;
