@@ -247,7 +247,8 @@ def kernel_timings(L, it, dev, copy_gbs):
                               device=dev)
             add_hbm(nm, lambda i, accs=accs, outs=outs, scale=scale, wsu=wsu, left=left: (lambda: binding.halo_dequant_unrotate(
                 accs[i], scale, had_block=hm, had_block_left=left, out=outs[i], workspace=wsu)), nbytes, k,
-                passes="row pass to fp32, then two strided passes" if left else None)
+                passes=("stand-alone entry point: strided passes from the int32 accumulators, then the row pass; inside the "
+                        "layer the product's epilogue runs the eight low strides and one strided pass is left") if left else None)
             del accs, outs
     return kernels
 

@@ -40,9 +40,15 @@ col_fwht_kernel(const void* in, int64_t ld_in, void* out, int64_t ld_out, int64_
     const int64_t hi = grp >> p;
     const int64_t base = (hi << (p + LOGR)) + lo;
     const int64_t stride = int64_t(1) << p;
+    // IN_I32: the scales of the wavefront's 2^LOGR rows, one per lane (lane t: row base + t * stride), handed out below
+    // with v_readlane (the row is the same for every lane, a vector load per row would repeat one address 64 times).
+    // Loaded before any lane leaves, so that every lane that is read from holds its value.
+    float my_scale = 1.0f;
+    if constexpr (IN == IN_I32) {
+        if (row_scale && lane < R) my_scale = row_scale[base + (int64_t)lane * stride];
+    }
     if (col >= cols) return;
     const bool pair_ok = (CPL == 1) || (col + 1 < cols);
-
     float v[R][CPL];
 #pragma unroll
     for (int t = 0; t < R; ++t) {
@@ -62,24 +68,7 @@ col_fwht_kernel(const void* in, int64_t ld_in, void* out, int64_t ld_out, int64_
                 v[t][0] = __uint_as_float((uint32_t)src[0] << 16);
             }
         } else if constexpr (IN == IN_I32) {
-            // accumulators of a product: (float(acc) * scale of the row) * tensor-wide scale, as the row kernel does
-            const int32_t* src = reinterpret_cast<const int32_t*>(in) + r * ld_in + col;
-            const float rs = row_scale ? row_scale[r] : 1.0f;
-            if constexpr (CPL == 2) {
-                if (pair_ok) {
-                    const int2 w = *reinterpret_cast<const int2*>(src);
-                    v[t][0] = (float)w.x * rs; v[t][1] = (float)w.y * rs;
-                } else {
-                    v[t][0] = (float)src[0] * rs; v[t][1] = 0.0f;
-                }
-            } else {
-                v[t][0] = (float)src[0] * rs;
-            }
-            if (post_scale) {
-                const float post = *post_scale;
-#pragma unroll
-                for (int c = 0; c < CPL; ++c) v[t][c] *= post;
-            }
+            // handled below: all loads first, then the conversion
         } else {
             const float* src = reinterpret_cast<const float*>(in) + r * ld_in + col;
             if constexpr (CPL == 2) {
@@ -92,6 +81,33 @@ col_fwht_kernel(const void* in, int64_t ld_in, void* out, int64_t ld_out, int64_
             } else {
                 v[t][0] = src[0];
             }
+        }
+    }
+
+    if constexpr (IN == IN_I32) {
+        // accumulators of a product: (float(acc) * scale of the row) * tensor-wide scale, as the row kernel does.  Every
+        // load is issued before the first conversion (one branch around the whole set, none inside it).
+        int raw[R][CPL];
+        const int32_t* src0 = reinterpret_cast<const int32_t*>(in) + base * ld_in + col;
+        if (CPL == 2 && pair_ok) {
+#pragma unroll
+            for (int t = 0; t < R; ++t) {
+                const int2 w = *reinterpret_cast<const int2*>(src0 + (int64_t)t * stride * ld_in);
+                raw[t][0] = w.x; raw[t][CPL - 1] = w.y;
+            }
+        } else {
+#pragma unroll
+            for (int t = 0; t < R; ++t) {
+                raw[t][0] = src0[(int64_t)t * stride * ld_in];
+                if (CPL == 2) raw[t][CPL - 1] = 0;
+            }
+        }
+        const float post = post_scale ? *post_scale : 1.0f;         // x * 1.0f is x
+#pragma unroll
+        for (int t = 0; t < R; ++t) {
+            const float rs = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(my_scale), t));
+#pragma unroll
+            for (int c = 0; c < CPL; ++c) v[t][c] = ((float)raw[t][c] * rs) * post;
         }
     }
 
