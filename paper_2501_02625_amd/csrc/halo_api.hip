@@ -111,19 +111,27 @@ BwdWorkspace bwd_layout(const halo_linear_desc* d) {
 // left block covers whole 256-row tiles and the product can take the 256 x 256 configuration (K = n in 64-byte steps).
 inline bool left_in_epilogue(int64_t b, int64_t n, int32_t hb) { return hb >= 256 && b % 256 == 0 && n % 64 == 0; }
 
-// The rest of that un-rotation: t [b x m] fp32 holds the product after the eight low left-hand strides.  Remaining
-// strides in place, then the row kernel (1/sqrt(left block), right-hand un-rotation, conversion).
+// The rest of that un-rotation: t [b x m] fp32 holds the product after the eight low left-hand strides.  Either one
+// kernel (top strides across the wavefronts of a workgroup, then each row's right-hand un-rotation), or the remaining
+// strides in place and then the row kernel (1/sqrt(left block), right-hand un-rotation, conversion).
 hipError_t finish_left_unrotation(float* t, int64_t b, int64_t m, int32_t hb, int32_t hm, void* out, halo_dtype odt,
                                   hipStream_t s) {
-    ColFwhtArgs c{t, IN_F32, m, t, OUT_F32, m, t, m, b, m, ilog2_exact(hb)};
-    c.first_stage = 8; c.skip_norm = 1;
-    hipError_t e = launch_col_fwht(c, s);
-    if (e != hipSuccess) return e;
     RowArgs r{};
     r.in = t; r.ld_in = m; r.rows = b; r.cols = m; r.out = out; r.ld_out = m;
     r.in_mul = (float)(1.0 / sqrt((double)hb));
     set_right_block(r, hm);
-    return launch_row_transform(r, IN_F32, odt == HALO_BF16 ? OUT_BF16 : OUT_F32, s);
+    const OutKind ok = odt == HALO_BF16 ? OUT_BF16 : OUT_F32;
+    // up to four top strides left and a right-hand block of 512 .. 2048: one kernel does the rest
+    const int top = ilog2_exact(hb) - 8;
+    if (r.kron_m == 0 && row_left_top_ok(b, m, r.log_block, top)) {
+        r.left_top = top;
+        return launch_row_left_top(r, ok, s);
+    }
+    ColFwhtArgs c{t, IN_F32, m, t, OUT_F32, m, t, m, b, m, ilog2_exact(hb)};
+    c.first_stage = 8; c.skip_norm = 1;
+    hipError_t e = launch_col_fwht(c, s);
+    if (e != hipSuccess) return e;
+    return launch_row_transform(r, IN_F32, ok, s);
 }
 
 }  // namespace

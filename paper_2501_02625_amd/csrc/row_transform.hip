@@ -19,6 +19,8 @@
 // 1/sqrt(d) factor at the end, which costs nothing.
 #pragma clang fp contract(off)
 
+#include <mutex>
+
 #include "halo_internal.h"
 
 namespace halo {
@@ -530,7 +532,120 @@ hipError_t launch_by_seg(const RowArgs& a, hipStream_t s) {
     }
 }
 
+// The end of a left+right un-rotation (see halo_internal.h).  Workgroup = 2^TOP wavefronts; wavefront t owns row
+// blk * hb + t * 256 + q of one right-hand block of 2^LOGSEG columns, hb = 256 << TOP: exactly the rows that the top TOP
+// strides of the left-hand rotation (256, 512, ...) combine.  Stage st pairs wavefront t with t ^ 2^st through LDS (the
+// lower row takes a + b, the upper one a - b), ascending; then the wavefront has its row of the left-rotated matrix in
+// registers, in the layout of the row kernel, and goes on as that kernel does.
+template <int LOGSEG, int OUT, int TOP>
+__global__ void __launch_bounds__(64 << TOP)
+row_left_top_kernel(RowArgs a, int segs, float c_norm) {
+    constexpr int LOGE = 2, EPL = 4;
+    constexpr int VPL = 1 << (LOGSEG - 6);
+    constexpr int NCH = VPL / EPL;
+    constexpr int SEG = 1 << LOGSEG;
+    extern __shared__ float s_xbuf[];        // [wavefront][value][lane]
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t g = (int64_t)blockIdx.x / segs;                 // group of 2^TOP rows: g = blk * 256 + q
+    const int seg = (int)((int64_t)blockIdx.x % segs);
+    const int64_t row = ((g >> 8) << (8 + TOP)) + ((int64_t)wave << 8) + (g & 255);
+    const int64_t kbase = (int64_t)seg * SEG + (int64_t)lane * EPL;
+
+    float v[VPL];
+    const float* src = reinterpret_cast<const float*>(a.in) + row * a.ld_in + kbase;
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+        const float4 q = *reinterpret_cast<const float4*>(src + c * 64 * EPL);
+        v[c * EPL + 0] = q.x; v[c * EPL + 1] = q.y; v[c * EPL + 2] = q.z; v[c * EPL + 3] = q.w;
+    }
+#pragma unroll
+    for (int st = 0; st < TOP; ++st) {
+        if (st > 0) __syncthreads();         // everyone has read the previous round
+#pragma unroll
+        for (int r = 0; r < VPL; ++r) s_xbuf[(wave * VPL + r) * 64 + lane] = v[r];
+        __syncthreads();
+        const bool upper = (wave >> st) & 1;
+        const int pw = wave ^ (1 << st);
+#pragma unroll
+        for (int r = 0; r < VPL; ++r) {
+            const float p = s_xbuf[(pw * VPL + r) * 64 + lane];
+            v[r] = upper ? p - v[r] : v[r] + p;
+        }
+    }
+    if (a.in_mul != 0.0f) {
+#pragma unroll
+        for (int r = 0; r < VPL; ++r) v[r] *= a.in_mul;
+    }
+    // right-hand un-rotation of the row (block = segment), as in row_phase1
+    const int bperm_addr = (lane ^ 32) << 2;
+    FwhtStages<VPL, LOGE, 0, LOGSEG>::run(v, LOGSEG, lane, bperm_addr);
+    const float c_l = (__builtin_popcount(lane) & 1) ? -c_norm : c_norm;     // the sign the lane stages leave behind
+#pragma unroll
+    for (int r = 0; r < VPL; ++r) v[r] *= c_l;
+
+    RowCtx x;
+    x.lane = lane; x.bperm_addr = bperm_addr; x.wave = wave; x.seg = seg; x.xbuf = s_xbuf;
+    x.row = row; x.kbase = kbase; x.row_ok = true;
+    row_phase2<LOGSEG, IN_F32, OUT, true>(a, x, v, 0.0f);
+}
+
+template <int LOGSEG, int OUT, int TOP>
+hipError_t launch_left_top(const RowArgs& a, hipStream_t s) {
+    constexpr int VPL = 1 << (LOGSEG - 6);
+    constexpr int kLds = (1 << TOP) * VPL * 64 * (int)sizeof(float);
+    static std::once_flag once;
+    static hipError_t attr_result = hipSuccess;
+    auto kern = row_left_top_kernel<LOGSEG, OUT, TOP>;
+    std::call_once(once, [&] {
+        if (kLds > 64 * 1024)
+            attr_result = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
+    });
+    if (attr_result != hipSuccess) return attr_result;
+    const int segs = (int)(a.cols >> LOGSEG);
+    const int64_t blocks = (a.rows >> TOP) * segs;
+    if (blocks <= 0 || blocks > 0x7FFFFFFF) return hipErrorInvalidValue;
+    const float c_norm = (float)(1.0 / sqrt((double)(int64_t(1) << LOGSEG)));
+    hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(64 << TOP), kLds, s, a, segs, c_norm);
+    return hipGetLastError();
+}
+
+template <int LOGSEG, int OUT>
+hipError_t launch_left_top_by_top(const RowArgs& a, hipStream_t s) {
+    switch (a.left_top) {
+        case 1: return launch_left_top<LOGSEG, OUT, 1>(a, s);
+        case 2: return launch_left_top<LOGSEG, OUT, 2>(a, s);
+        case 3: return launch_left_top<LOGSEG, OUT, 3>(a, s);
+        case 4: return launch_left_top<LOGSEG, OUT, 4>(a, s);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+template <int OUT>
+hipError_t launch_left_top_by_seg(const RowArgs& a, hipStream_t s) {
+    switch (a.log_block) {
+        case 9: return launch_left_top_by_top<9, OUT>(a, s);
+        case 10: return launch_left_top_by_top<10, OUT>(a, s);
+        case 11: return launch_left_top_by_top<11, OUT>(a, s);
+        default: return hipErrorInvalidValue;
+    }
+}
+
 }  // namespace
+
+bool row_left_top_ok(int64_t rows, int64_t cols, int log_block, int left_top) {
+    if (log_block < 9 || log_block > 11 || left_top < 1 || left_top > 4) return false;
+    if (rows <= 0 || cols <= 0 || cols % (int64_t(1) << log_block) != 0) return false;
+    return rows % (int64_t(256) << left_top) == 0;
+}
+
+hipError_t launch_row_left_top(const RowArgs& a, OutKind out, hipStream_t s) {
+    if (a.kron_m != 0 || a.fold || a.rows2 != 0 || !row_left_top_ok(a.rows, a.cols, a.log_block, a.left_top))
+        return hipErrorInvalidValue;
+    if (out == OUT_BF16) return launch_left_top_by_seg<OUT_BF16>(a, s);
+    if (out == OUT_F32) return launch_left_top_by_seg<OUT_F32>(a, s);
+    return hipErrorInvalidValue;
+}
 
 hipError_t launch_row_transform(const RowArgs& a, InKind in, OutKind out, hipStream_t s) {
     if ((a.rows == 0 && a.rows2 == 0) || a.cols == 0) return hipSuccess;

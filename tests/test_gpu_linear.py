@@ -100,6 +100,20 @@ def test_small_layers_all_levels(b, m, n, level):
     run_and_check(b, m, n, level, Xb, Wb, Eb)
 
 
+@pytest.mark.parametrize("b,m,n,hm,hb,odt", [
+    (1024, 1024, 256, 0, 0, torch.float32),        # left block 1024: two top strides after the epilogue's eight; right block 1024
+    (2048, 2048, 128, 0, 0, torch.bfloat16),       # three top strides, right block 2048
+    (4096, 512, 64, 0, 0, torch.float32),          # four top strides, right block 512
+    (1024, 1536, 192, 512, 512, torch.float32),    # two left blocks of 512 (one top stride), three right blocks of 512
+    (8192, 512, 64, 0, 0, torch.float32),          # left block 8192: five strides left, the strided pass takes them
+    (768, 1024, 128, 0, 0, torch.float32),         # b = 3 * 256: left block 256, nothing left after the epilogue
+])
+def test_level2_output_side_variants(b, m, n, hm, hb, odt):
+    """Level 2 with the low left-hand strides in the product's epilogue: every way the rest of the un-rotation can go."""
+    Xb = inputs.make_activations(b, m, 0.01, b + m); Wb = inputs.make_weights(n, m, b + m); Eb = inputs.make_errors(b, n, b + m)
+    run_and_check(b, m, n, 2, Xb, Wb, Eb, odt=odt, hm=hm, hb=hb)
+
+
 def test_bf16_outputs_and_explicit_blocks():
     b, m, n = 256, 1024, 384
     Xb = inputs.make_activations(b, m, 0.01, 1); Wb = inputs.make_weights(n, m, 1); Eb = inputs.make_errors(b, n, 1)
