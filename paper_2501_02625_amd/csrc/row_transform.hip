@@ -538,13 +538,13 @@ hipError_t launch_by_seg(const RowArgs& a, hipStream_t s) {
 // lower row takes a + b, the upper one a - b), ascending; then the wavefront has its row of the left-rotated matrix in
 // registers, in the layout of the row kernel, and goes on as that kernel does.
 template <int LOGSEG, int OUT, int TOP>
-__global__ void __launch_bounds__(64 << TOP)
+__global__ void __launch_bounds__(64 << TOP, 8)
 row_left_top_kernel(RowArgs a, int segs, float c_norm) {
     constexpr int LOGE = 2, EPL = 4;
     constexpr int VPL = 1 << (LOGSEG - 6);
     constexpr int NCH = VPL / EPL;
     constexpr int SEG = 1 << LOGSEG;
-    extern __shared__ float s_xbuf[];        // [wavefront][value][lane]
+    extern __shared__ __align__(16) float s_exch[];        // exchange buffer of the stages across wavefronts
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t g = (int64_t)blockIdx.x / segs;                 // group of 2^TOP rows: g = blk * 256 + q
@@ -559,18 +559,31 @@ row_left_top_kernel(RowArgs a, int segs, float c_norm) {
         const float4 q = *reinterpret_cast<const float4*>(src + c * 64 * EPL);
         v[c * EPL + 0] = q.x; v[c * EPL + 1] = q.y; v[c * EPL + 2] = q.z; v[c * EPL + 3] = q.w;
     }
+    // Exchange buffer: [wavefront][value / 4][lane][4] (16-byte LDS accesses), HALF values per wavefront at a time so that
+    // two workgroups fit one compute unit's LDS and one of them can load while the other exchanges.
+    constexpr int HALF = VPL > 16 ? VPL / 2 : VPL;
+    float4* xb = reinterpret_cast<float4*>(s_exch);
+    bool first_round = true;
 #pragma unroll
     for (int st = 0; st < TOP; ++st) {
-        if (st > 0) __syncthreads();         // everyone has read the previous round
-#pragma unroll
-        for (int r = 0; r < VPL; ++r) s_xbuf[(wave * VPL + r) * 64 + lane] = v[r];
-        __syncthreads();
         const bool upper = (wave >> st) & 1;
         const int pw = wave ^ (1 << st);
 #pragma unroll
-        for (int r = 0; r < VPL; ++r) {
-            const float p = s_xbuf[(pw * VPL + r) * 64 + lane];
-            v[r] = upper ? p - v[r] : v[r] + p;
+        for (int h0 = 0; h0 < VPL; h0 += HALF) {
+            if (!first_round) __syncthreads();   // everyone has read the previous round
+            first_round = false;
+#pragma unroll
+            for (int r = 0; r < HALF; r += 4)
+                xb[(wave * (HALF / 4) + r / 4) * 64 + lane] = make_float4(v[h0 + r], v[h0 + r + 1], v[h0 + r + 2], v[h0 + r + 3]);
+            __syncthreads();
+#pragma unroll
+            for (int r = 0; r < HALF; r += 4) {
+                const float4 p = xb[(pw * (HALF / 4) + r / 4) * 64 + lane];
+                v[h0 + r + 0] = upper ? p.x - v[h0 + r + 0] : v[h0 + r + 0] + p.x;
+                v[h0 + r + 1] = upper ? p.y - v[h0 + r + 1] : v[h0 + r + 1] + p.y;
+                v[h0 + r + 2] = upper ? p.z - v[h0 + r + 2] : v[h0 + r + 2] + p.z;
+                v[h0 + r + 3] = upper ? p.w - v[h0 + r + 3] : v[h0 + r + 3] + p.w;
+            }
         }
     }
     if (a.in_mul != 0.0f) {
@@ -585,7 +598,7 @@ row_left_top_kernel(RowArgs a, int segs, float c_norm) {
     for (int r = 0; r < VPL; ++r) v[r] *= c_l;
 
     RowCtx x;
-    x.lane = lane; x.bperm_addr = bperm_addr; x.wave = wave; x.seg = seg; x.xbuf = s_xbuf;
+    x.lane = lane; x.bperm_addr = bperm_addr; x.wave = wave; x.seg = seg; x.xbuf = s_exch;
     x.row = row; x.kbase = kbase; x.row_ok = true;
     row_phase2<LOGSEG, IN_F32, OUT, true>(a, x, v, 0.0f);
 }
@@ -593,7 +606,7 @@ row_left_top_kernel(RowArgs a, int segs, float c_norm) {
 template <int LOGSEG, int OUT, int TOP>
 hipError_t launch_left_top(const RowArgs& a, hipStream_t s) {
     constexpr int VPL = 1 << (LOGSEG - 6);
-    constexpr int kLds = (1 << TOP) * VPL * 64 * (int)sizeof(float);
+    constexpr int kLds = (1 << TOP) * (VPL > 16 ? VPL / 2 : VPL) * 64 * (int)sizeof(float);
     static std::once_flag once;
     static hipError_t attr_result = hipSuccess;
     auto kern = row_left_top_kernel<LOGSEG, OUT, TOP>;
