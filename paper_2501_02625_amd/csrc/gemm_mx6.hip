@@ -15,6 +15,7 @@
 // scale dword per thread) while the current one is multiplied, then registers -> LDS, one barrier per K step.  A lane
 // reads its block as three 8-byte LDS loads: the code bytes in memory are the register image, nothing is unpacked.
 #include <mutex>
+#include <type_traits>
 
 #include "halo_internal.h"
 
@@ -181,6 +182,13 @@ constexpr int kBigLoads = 7;                                // DMA instructions 
 constexpr int kBigEpiPitch = 64 + 8;
 constexpr int kBigLds = kBigNS * kBigStage;
 static_assert(kBigLds <= 160 * 1024 && 8 * 32 * kBigEpiPitch * 4 <= kBigLds, "LDS budget");
+// WIDE form (K a multiple of 512, 16-byte aligned scale rows): the stages hold codes only, and the scale bytes of FOUR K
+// steps travel as one 16-byte chunk per row into one of two buffers behind the stages - a quarter of the scale requests,
+// each of which touches 64 different cache lines.
+constexpr int kWideStage = 2 * kBigOpBytes;
+constexpr int kWideScaleOff = kBigNS * kWideStage;
+constexpr int kWideLds = kWideScaleOff + 2 * 512 * 16;
+static_assert(kWideLds <= 160 * 1024, "LDS budget");
 
 #define HALO_GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void*)(p))
 #define HALO_LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
@@ -241,7 +249,9 @@ __device__ __forceinline__ void big_mma(const BigFrags& f, const int (&sca)[4], 
                                                                         2 * KS, sca[i], 2 * KS, scb[j]);
 }
 
+template <bool WIDE>
 __global__ void __launch_bounds__(512) gemm_mx6_big_kernel(Mx6GemmArgs a, int tiles_m, int tiles_n) {
+    constexpr int kStage = WIDE ? kWideStage : kBigStage;
     extern __shared__ __align__(16) unsigned char smem_big[];
     unsigned char* smem = smem_big;
     const int tid = threadIdx.x;
@@ -290,8 +300,10 @@ __global__ void __launch_bounds__(512) gemm_mx6_big_kernel(Mx6GemmArgs a, int ti
         if (tid < 256) { gr = m0 + tid; gr = gr < a.M ? gr : a.M - 1; s_src = a.SA + gr * a.ldsa; }
         else { gr = n0 + tid - 256; gr = gr < a.N ? gr : a.N - 1; s_src = a.SB + gr * a.ldsb; }
     }
-    auto issue_dma = [&](int t, int src) {
-        unsigned char* st = smem + (t % kBigNS) * kBigStage;
+    // K step t (codes of step `src`) into ring slot t % NS.  with_scales: in the WIDE form, also the scale chunk of the
+    // group of four K steps that starts at t (t a multiple of 4) into scale buffer (t / 4) % 2.
+    auto issue_dma = [&](int t, int src, bool with_scales) {
+        unsigned char* st = smem + (t % kBigNS) * kStage;
 #pragma unroll
         for (int i = 0; i < 3; ++i)
             __builtin_amdgcn_global_load_lds(HALO_GLOBAL_PTR(a_src[i] + (int64_t)src * 96),
@@ -300,8 +312,14 @@ __global__ void __launch_bounds__(512) gemm_mx6_big_kernel(Mx6GemmArgs a, int ti
         for (int i = 0; i < 3; ++i)
             __builtin_amdgcn_global_load_lds(HALO_GLOBAL_PTR(b_src[i] + (int64_t)src * 96),
                                              HALO_LDS_PTR(st + kBigOpBytes + (wave * 64 + i * 512) * 16), 16, 0, 0);
-        __builtin_amdgcn_global_load_lds(HALO_GLOBAL_PTR(s_src + (int64_t)src * 4),
-                                         HALO_LDS_PTR(st + kBigScaleOff + wave * 64 * 4), 4, 0, 0);
+        if constexpr (!WIDE) {
+            __builtin_amdgcn_global_load_lds(HALO_GLOBAL_PTR(s_src + (int64_t)src * 4),
+                                             HALO_LDS_PTR(st + kBigScaleOff + wave * 64 * 4), 4, 0, 0);
+        } else if (with_scales) {
+            const int g = src / 4;
+            __builtin_amdgcn_global_load_lds(HALO_GLOBAL_PTR(s_src + (int64_t)g * 16),
+                                             HALO_LDS_PTR(smem + kWideScaleOff + ((t / 4) & 1) * 8192 + wave * 64 * 16), 16, 0, 0);
+        }
     };
 
     // ---- this lane's three 8-byte pieces of K block 2 * ks + half, as byte offsets inside a stage
@@ -315,8 +333,9 @@ __global__ void __launch_bounds__(512) gemm_mx6_big_kernel(Mx6GemmArgs a, int ti
             off_a[ks][j] = (uint32_t)(wave_m * 4 * 3072) + in_block;
             off_b[ks][j] = (uint32_t)(kBigOpBytes + wave_n * 2 * 3072) + in_block;
         }
-    off_sa = (uint32_t)(kBigScaleOff + (wave_m * 128 + lrow) * 4);
-    off_sb = (uint32_t)(kBigScaleOff + (256 + wave_n * 64 + lrow) * 4);
+    off_sa = WIDE ? (uint32_t)(kWideScaleOff + (wave_m * 128 + lrow) * 16) : (uint32_t)(kBigScaleOff + (wave_m * 128 + lrow) * 4);
+    off_sb = WIDE ? (uint32_t)(kWideScaleOff + (256 + wave_n * 64 + lrow) * 16)
+                  : (uint32_t)(kBigScaleOff + (256 + wave_n * 64 + lrow) * 4);
     const uint32_t lds0 = (uint32_t)(uintptr_t)HALO_LDS_PTR(smem);
 
     v16f acc[4][2];
@@ -329,14 +348,18 @@ __global__ void __launch_bounds__(512) gemm_mx6_big_kernel(Mx6GemmArgs a, int ti
 
     if (nk > 0) {
         constexpr int D = kBigNS - 1;
-        for (int t = 0; t < D; ++t) issue_dma(t, t < nk ? t : nk - 1);
-        for (int kt = 0; kt < nk; ++kt) {
-            asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"((D - 1) * kBigLoads) : "memory");
+        // One K step.  PH: kt % 4 in the WIDE form (it fixes which steps carry a scale chunk, hence the wait count and the
+        // byte of the chunk to use), -1 otherwise.
+        auto k_step = [&](auto ph, int kt) {
+            constexpr int PH = decltype(ph)::value;
+            // outstanding afterwards: the loads of step kt + 1 only (6 code chunks, plus its scale request)
+            constexpr int kAllowed = WIDE ? (PH == 3 ? 7 : 6) : (D - 1) * kBigLoads;
+            asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(kAllowed) : "memory");
             __builtin_amdgcn_s_barrier();
             asm volatile("" ::: "memory");
             // ring slot (kt - 1) % NS: everyone is past reading it
-            issue_dma(kt + D, kt + D < nk ? kt + D : nk - 1);
-            const uint32_t st = lds0 + (uint32_t)((kt % kBigNS) * kBigStage);
+            issue_dma(kt + D, kt + D < nk ? kt + D : nk - 1, PH == 2);
+            const uint32_t st = lds0 + (uint32_t)((kt % kBigNS) * kStage);
             uint32_t addr_a[2][3], addr_b[2][3];
 #pragma unroll
             for (int ks = 0; ks < 2; ++ks)
@@ -344,10 +367,18 @@ __global__ void __launch_bounds__(512) gemm_mx6_big_kernel(Mx6GemmArgs a, int ti
                 for (int j = 0; j < 3; ++j) { addr_a[ks][j] = st + off_a[ks][j]; addr_b[ks][j] = st + off_b[ks][j]; }
             // the four scale bytes of each of this lane's six rows (same inline-assembly reasoning as the fragments)
             int sca[4], scb[2];
-            asm volatile("ds_read_b32 %0, %6\n\tds_read_b32 %1, %6 offset:128\n\tds_read_b32 %2, %6 offset:256\n\t"
-                         "ds_read_b32 %3, %6 offset:384\n\tds_read_b32 %4, %7\n\tds_read_b32 %5, %7 offset:128"
-                         : "=&v"(sca[0]), "=&v"(sca[1]), "=&v"(sca[2]), "=&v"(sca[3]), "=&v"(scb[0]), "=&v"(scb[1])
-                         : "v"(st + off_sa), "v"(st + off_sb));
+            if constexpr (WIDE) {
+                const uint32_t sbase = lds0 + (uint32_t)(((kt / 4) & 1) * 8192 + PH * 4);
+                asm volatile("ds_read_b32 %0, %6\n\tds_read_b32 %1, %6 offset:512\n\tds_read_b32 %2, %6 offset:1024\n\t"
+                             "ds_read_b32 %3, %6 offset:1536\n\tds_read_b32 %4, %7\n\tds_read_b32 %5, %7 offset:512"
+                             : "=&v"(sca[0]), "=&v"(sca[1]), "=&v"(sca[2]), "=&v"(sca[3]), "=&v"(scb[0]), "=&v"(scb[1])
+                             : "v"(sbase + off_sa), "v"(sbase + off_sb));
+            } else {
+                asm volatile("ds_read_b32 %0, %6\n\tds_read_b32 %1, %6 offset:128\n\tds_read_b32 %2, %6 offset:256\n\t"
+                             "ds_read_b32 %3, %6 offset:384\n\tds_read_b32 %4, %7\n\tds_read_b32 %5, %7 offset:128"
+                             : "=&v"(sca[0]), "=&v"(sca[1]), "=&v"(sca[2]), "=&v"(sca[3]), "=&v"(scb[0]), "=&v"(scb[1])
+                             : "v"(st + off_sa), "v"(st + off_sb));
+            }
             BigFrags f0, f1;
             big_load_frags<0>(addr_a, addr_b, f0);
             big_wait_frags(f0);              // the hardware counts at most 15 outstanding LDS reads: no partial wait here
@@ -360,6 +391,20 @@ __global__ void __launch_bounds__(512) gemm_mx6_big_kernel(Mx6GemmArgs a, int ti
             big_mma<0>(f0, sca, scb, acc);
             big_wait_frags(f1);
             big_mma<1>(f1, sca, scb, acc);
+        };
+        if constexpr (WIDE) {
+            // nk is a multiple of 4 here.  Step 0 carries the first scale chunk; step 1 none.
+            issue_dma(0, 0, true);
+            issue_dma(1, 1, false);
+            for (int kt = 0; kt < nk; kt += 4) {
+                k_step(std::integral_constant<int, 0>{}, kt);
+                k_step(std::integral_constant<int, 1>{}, kt + 1);
+                k_step(std::integral_constant<int, 2>{}, kt + 2);
+                k_step(std::integral_constant<int, 3>{}, kt + 3);
+            }
+        } else {
+            for (int t = 0; t < D; ++t) issue_dma(t, t < nk ? t : nk - 1, false);
+            for (int kt = 0; kt < nk; ++kt) k_step(std::integral_constant<int, -1>{}, kt);
         }
         asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
     }
@@ -425,12 +470,21 @@ hipError_t launch_gemm_mx6(const Mx6GemmArgs& a, hipStream_t s) {
         static std::once_flag once;
         static hipError_t attr_result = hipSuccess;
         std::call_once(once, [&] {
-            attr_result = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_mx6_big_kernel),
+            attr_result = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_mx6_big_kernel<false>),
                                               hipFuncAttributeMaxDynamicSharedMemorySize, kBigLds);
+            if (attr_result == hipSuccess)
+                attr_result = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_mx6_big_kernel<true>),
+                                                  hipFuncAttributeMaxDynamicSharedMemorySize, kWideLds);
         });
         if (attr_result != hipSuccess) return attr_result;
-        hipLaunchKernelGGL(gemm_mx6_big_kernel, dim3((unsigned)(big_m * big_n)), dim3(512), kBigLds, s, a, (int)big_m,
-                           (int)big_n);
+        const bool wide = a.K % 512 == 0 && a.ldsa % 16 == 0 && a.ldsb % 16 == 0 &&
+                          (reinterpret_cast<uintptr_t>(a.SA) & 15u) == 0 && (reinterpret_cast<uintptr_t>(a.SB) & 15u) == 0;
+        if (wide)
+            hipLaunchKernelGGL(gemm_mx6_big_kernel<true>, dim3((unsigned)(big_m * big_n)), dim3(512), kWideLds, s, a, (int)big_m,
+                               (int)big_n);
+        else
+            hipLaunchKernelGGL(gemm_mx6_big_kernel<false>, dim3((unsigned)(big_m * big_n)), dim3(512), kBigLds, s, a, (int)big_m,
+                               (int)big_n);
         return hipGetLastError();
     }
     const int64_t tiles_m = (a.M + 127) / 128, tiles_n = (a.N + 127) / 128;

@@ -49,7 +49,9 @@ def test_mx6_quantiser_zero_blocks_tiny_and_huge_values():
 
 @pytest.mark.parametrize("M,N,K", [(128, 128, 128), (200, 136, 512), (64, 300, 4096), (512, 512, 1024),
                                    (4000, 3100, 256),      # ragged, enough 256 x 256 tiles for the DMA kernel
-                                   (3584, 3584, 128)])     # one K step: the ring never fills
+                                   (3584, 3584, 128),      # one K step: the ring never fills
+                                   (3600, 3330, 1024),     # ragged, K a multiple of 512: scale bytes of four K steps per request
+                                   (4096, 3072, 512)])     # one group of four K steps
 def test_mx6_gemm_against_exact_product(M, N, K):
     Xb = inputs.make_activations(M, K, 0.01, M + N); Wb = inputs.make_weights(N, K, M + N)
     hb = K & -K if K <= 4096 else 0
