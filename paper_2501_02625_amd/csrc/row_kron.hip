@@ -193,7 +193,7 @@ row_kron28_kernel(RowArgs a, float c_norm, unsigned blocks1) {
     if constexpr (OUT == OUT_Q8) {
         float amax = 0.0f;
 #pragma unroll
-        for (int j = 0; j < kM; j += 2) amax = __builtin_fmaxf(amax, __builtin_fmaxf(fabsf(v[j]), fabsf(v[j + 1])));
+        for (int j = 0; j < kM; j += 2) asm("v_max3_f32 %0, %0, |%1|, |%2|" : "+v"(amax) : "v"(v[j]), "v"(v[j + 1]));
         amax = __builtin_fmaxf(amax, lane_xor<0>(amax, bperm_addr));
         amax = __builtin_fmaxf(amax, lane_xor<1>(amax, bperm_addr));
         amax = __builtin_fmaxf(amax, lane_xor<2>(amax, bperm_addr));

@@ -274,8 +274,15 @@ __device__ __forceinline__ float row_phase1(const RowArgs& a, const RowCtx& x, f
 
     float amax = 0.0f;
     if constexpr (OUT == OUT_Q8) {
+        // one v_max3_f32 with |.| source modifiers per pair of values (written out: the compiler's fmaxf chain takes
+        // four instructions per pair), in two chains
+        float amax2 = 0.0f;
 #pragma unroll
-        for (int r = 0; r < VPL; r += 2) amax = __builtin_fmaxf(amax, __builtin_fmaxf(fabsf(v[r]), fabsf(v[r + 1])));
+        for (int r = 0; r < VPL; r += 4) {
+            asm("v_max3_f32 %0, %0, |%1|, |%2|" : "+v"(amax) : "v"(v[r]), "v"(v[r + 1]));
+            asm("v_max3_f32 %0, %0, |%1|, |%2|" : "+v"(amax2) : "v"(v[r + 2]), "v"(v[r + 3]));
+        }
+        amax = __builtin_fmaxf(amax, amax2);
         amax = wave_max(amax, x.bperm_addr);
     }
     return amax;
