@@ -18,11 +18,6 @@ namespace {
 // for the device address once per device (static_scratch_address) and passes that to the kernels.
 static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
-__device__ __forceinline__ uint32_t f32_to_bf16_rne(float f) {
-    const uint32_t u = __float_as_uint(f);
-    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
-}
-
 // ------------------------------------------------------------------------------------------------
 // One pass of the left-hand FWHT: stages with row strides 2^p .. 2^(p+LOGR-1), ascending.
 // A wavefront owns 64*CPL consecutive columns and the 2^LOGR rows  base + t*2^p.
@@ -148,10 +143,10 @@ col_fwht_kernel(const void* in, int64_t ld_in, void* out, int64_t ld_out, int64_
         } else {
             uint16_t* dst = reinterpret_cast<uint16_t*>(out) + r * ld_out + col;
             if constexpr (CPL == 2) {
-                if (pair_ok) *reinterpret_cast<uint32_t*>(dst) = f32_to_bf16_rne(v[t][0]) | (f32_to_bf16_rne(v[t][1]) << 16);
-                else dst[0] = (uint16_t)f32_to_bf16_rne(v[t][0]);
+                if (pair_ok) *reinterpret_cast<uint32_t*>(dst) = pack_bf16x2(v[t][0], v[t][1]);
+                else dst[0] = bf16_bits(v[t][0]);
             } else {
-                dst[0] = (uint16_t)f32_to_bf16_rne(v[t][0]);
+                dst[0] = bf16_bits(v[t][0]);
             }
         }
     }

@@ -55,11 +55,6 @@ typedef int v2i __attribute__((ext_vector_type(2)));
 #define HALO_GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void*)(p))
 #define HALO_LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
 
-__device__ __forceinline__ uint32_t f32_to_bf16_rne(float f) {
-    const uint32_t u = __float_as_uint(f);
-    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
-}
-
 // TR: the K-strided B operand goes to LDS untransposed (K-major rows of BN bytes, by DMA like A) and is transposed
 // by the LDS read itself (ds_read_b64_tr_b8).  !TRANSB && !TR: B is transposed in registers (staged loop only).
 template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, bool TRANSB, int NS, bool TR = false>
@@ -339,12 +334,12 @@ __device__ __forceinline__ void epilogue(const GemmArgs& a, int64_t m0, int64_t 
                 } else {
                     uint16_t* dst = reinterpret_cast<uint16_t*>(a.C) + row * a.ldc + col;
                     if (col_all) {
-                        *reinterpret_cast<uint2*>(dst) = make_uint2(f32_to_bf16_rne(f[0]) | (f32_to_bf16_rne(f[1]) << 16),
-                                                                     f32_to_bf16_rne(f[2]) | (f32_to_bf16_rne(f[3]) << 16));
+                        *reinterpret_cast<uint2*>(dst) = make_uint2(pack_bf16x2(f[0], f[1]),
+                                                                     pack_bf16x2(f[2], f[3]));
                     } else {
 #pragma unroll
                         for (int e = 0; e < 4; ++e)
-                            if (col + e < a.N) dst[e] = (uint16_t)f32_to_bf16_rne(f[e]);
+                            if (col + e < a.N) dst[e] = bf16_bits(f[e]);
                     }
                 }
             }

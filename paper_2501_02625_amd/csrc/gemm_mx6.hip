@@ -31,11 +31,6 @@ constexpr int kPitch = 112;                         // LDS bytes per row and K s
 constexpr int kCodeBytes = 256 * kPitch;            // 128 rows of A, then 128 rows of B
 constexpr int kStageBytes = kCodeBytes + 256 * 4;   // + one dword of four scale bytes per row
 
-__device__ __forceinline__ uint32_t f32_to_bf16_rne(float f) {
-    const uint32_t u = __float_as_uint(f);
-    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
-}
-
 __global__ void __launch_bounds__(256, 2) gemm_mx6_kernel(Mx6GemmArgs a, int tiles_n) {
     __shared__ __align__(16) unsigned char smem[2 * kStageBytes];
     const int tid = threadIdx.x;
@@ -154,7 +149,7 @@ __global__ void __launch_bounds__(256, 2) gemm_mx6_kernel(Mx6GemmArgs a, int til
                 const int64_t row = m0 + wave_m * 64 + i * 16 + 4 * g + r;
                 if (row >= a.M) continue;
                 if (a.c_is_f32) reinterpret_cast<float*>(a.C)[row * a.ldc + col] = acc[i][j][r];
-                else reinterpret_cast<uint16_t*>(a.C)[row * a.ldc + col] = (uint16_t)f32_to_bf16_rne(acc[i][j][r]);
+                else reinterpret_cast<uint16_t*>(a.C)[row * a.ldc + col] = bf16_bits(acc[i][j][r]);
             }
         }
 }
@@ -445,12 +440,12 @@ __global__ void __launch_bounds__(512) gemm_mx6_big_kernel(Mx6GemmArgs a, int ti
             } else {
                 uint16_t* dst = reinterpret_cast<uint16_t*>(a.C) + row * a.ldc + col;
                 if (col_all) {
-                    *reinterpret_cast<uint2*>(dst) = make_uint2(f32_to_bf16_rne(f[0]) | (f32_to_bf16_rne(f[1]) << 16),
-                                                                 f32_to_bf16_rne(f[2]) | (f32_to_bf16_rne(f[3]) << 16));
+                    *reinterpret_cast<uint2*>(dst) = make_uint2(pack_bf16x2(f[0], f[1]),
+                                                                 pack_bf16x2(f[2], f[3]));
                 } else {
 #pragma unroll
                     for (int e = 0; e < 4; ++e)
-                        if (col + e < a.N) dst[e] = (uint16_t)f32_to_bf16_rne(f[e]);
+                        if (col + e < a.N) dst[e] = bf16_bits(f[e]);
                 }
             }
         }

@@ -162,6 +162,15 @@ struct Mx6GemmArgs {
 };
 hipError_t launch_gemm_mx6(const Mx6GemmArgs& a, hipStream_t s);
 
+// fp32 -> bf16, round to nearest even, on the hardware conversion (v_cvt_pk_bf16_f32: two values per instruction).
+typedef __bf16 halo_bf16x2 __attribute__((ext_vector_type(2)));
+typedef float halo_f32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+    const halo_f32x2 v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, halo_bf16x2));
+}
+__device__ __forceinline__ uint16_t bf16_bits(float f) { return __builtin_bit_cast(uint16_t, (__bf16)f); }
+
 inline int ilog2_exact(int64_t v) {
     int l = 0;
     while ((int64_t(1) << l) < v) ++l;

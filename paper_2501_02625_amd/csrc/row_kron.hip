@@ -92,11 +92,6 @@ __device__ __forceinline__ void stage_across_lanes(float (&v)[kM], int lane, int
     }
 }
 
-__device__ __forceinline__ uint32_t f32_to_bf16_rne(float f) {
-    const uint32_t u = __float_as_uint(f);
-    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
-}
-
 // LOGP: log2 of the Walsh-Hadamard factor (6 .. 9); a Hadamard block is 28 * 2^LOGP elements = 2^(LOGP-6) wavefronts.
 template <int IN, int OUT, int LOGP>
 __global__ void __launch_bounds__(512)
@@ -230,8 +225,8 @@ row_kron28_kernel(RowArgs a, float c_norm, unsigned blocks1) {
         uint2* dst = reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(a.out) + row * a.ld_out + k0);
 #pragma unroll
         for (int q = 0; q < kM / 4; ++q)
-            dst[q] = make_uint2(f32_to_bf16_rne(v[4 * q]) | (f32_to_bf16_rne(v[4 * q + 1]) << 16),
-                                f32_to_bf16_rne(v[4 * q + 2]) | (f32_to_bf16_rne(v[4 * q + 3]) << 16));
+            dst[q] = make_uint2(pack_bf16x2(v[4 * q], v[4 * q + 1]),
+                                pack_bf16x2(v[4 * q + 2], v[4 * q + 3]));
     } else {
         float4* dst = reinterpret_cast<float4*>(reinterpret_cast<float*>(a.out) + row * a.ld_out + k0);
 #pragma unroll

@@ -58,11 +58,6 @@ __device__ __forceinline__ float wave_max(float x, int bperm_addr) {
     return x;
 }
 
-__device__ __forceinline__ uint32_t f32_to_bf16_rne(float f) {
-    const uint32_t u = __float_as_uint(f);
-    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
-}
-
 template <int VPL, int RB>
 __device__ __forceinline__ void stage_in_regs(float (&v)[VPL]) {
     constexpr int H = 1 << RB;
@@ -380,7 +375,7 @@ __device__ __forceinline__ void row_phase2(const RowArgs& a, const RowCtx& x, co
             uint32_t packed[EPL / 2];
 #pragma unroll
             for (int i = 0; i < EPL / 2; ++i)
-                packed[i] = f32_to_bf16_rne(v[c * EPL + 2 * i]) | (f32_to_bf16_rne(v[c * EPL + 2 * i + 1]) << 16);
+                packed[i] = pack_bf16x2(v[c * EPL + 2 * i], v[c * EPL + 2 * i + 1]);
             if (FAST || (x.row_ok && k0 + EPL <= a.cols)) {
                 if constexpr (EPL == 8) {
                     *reinterpret_cast<uint4*>(orow + k0) = make_uint4(packed[0], packed[1], packed[2], packed[3]);

@@ -180,6 +180,21 @@ def test_dequant_unrotate(rows, cols, hb, hbl, odt):
         gu.assert_bf16_within_one_ulp(out, T, "unrotated bf16")
 
 
+def test_bf16_outputs_round_to_nearest_even_exactly():
+    """bf16 stores go through the hardware conversion: integers that lie exactly between two bf16 values (and random
+    ones) must come out as the oracle's round-to-nearest-even, bit for bit."""
+    rng = np.random.default_rng(12)
+    ties = np.array([257, 259, 261, 263, 513 * 2, 515 * 2, -257, -259, (1 << 16) + 128, (1 << 16) + 384, 3, 0, -1, 1 << 23],
+                    dtype=np.int32)
+    acc = rng.integers(-(1 << 24), 1 << 24, size=(64, 512), dtype=np.int32)
+    acc[0, :ties.size] = ties
+    acc[1] = (rng.integers(1, 1 << 15, size=512) * 2 + 1).astype(np.int32) << 7      # odd multiples of 128: all ties
+    out = binding.halo_dequant_unrotate(gu.to_dev(acc), None, had_block=0, out_dtype=torch.bfloat16)
+    want = orc.real_to_bf16_bits(acc.astype(np.float32))
+    got = gu.dev_bf16_to_bits(out[:, :512].contiguous())
+    assert np.array_equal(got, want), int(np.sum(got != want))
+
+
 def test_repeatability_same_bits_twice():
     bits = inputs.make_activations(300, 4096, 0.001, 9)
     x = gu.bits_to_dev(bits)
