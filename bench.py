@@ -36,7 +36,7 @@ def parse():
     p.add_argument("--steps", type=int, default=100)
     p.add_argument("--warmup", type=int, default=20)
     p.add_argument("--config", default="c2", help="headline workload: c2 (default) or c3")
-    p.add_argument("--extra-configs", default="c3,c4,c5,c6", help="comma list of further configs reported under `configs`")
+    p.add_argument("--extra-configs", default="c3,c4,c5,c6,c7", help="comma list of further configs reported under `configs`")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--kernel-iters", type=int, default=50, help="launches per kernel for the per-kernel timings")
     p.add_argument("--pmc-target", default="",
@@ -111,7 +111,8 @@ class Linear:
         self.host["W"] = inputs.make_weights(n, m, sub)
         self.host["E"] = inputs.make_errors(b, n, sub)
         self.W, self.E = to_dev(self.host["W"]), to_dev(self.host["E"])
-        self.desc = binding.make_desc(b, m, n, self.level, torch.bfloat16, had_block_m=self.hm)
+        self.desc = binding.make_desc(b, m, n, self.level, torch.bfloat16, had_block_m=self.hm,
+                                      scale_mode=binding.HALO_SCALE_PER_TENSOR if cfg.per_tensor else binding.HALO_SCALE_PER_ROW)
         self.state = binding.LinearState(Xq, s_x, torch.empty((n, m), dtype=torch.int8, device=dev),
                                          torch.empty((n,), dtype=torch.float32, device=dev))
         alloc = lambda key, shape: (out_bufs.setdefault(key, torch.empty(shape, dtype=torch.bfloat16, device=dev))
@@ -122,8 +123,8 @@ class Linear:
         self.ws_bytes = binding.halo_linear_workspace_bytes(self.desc)
         self.ops = 6.0 * b * n * m
 
-    def fwd(self, binding):
-        binding.halo_linear_fwd(self.desc, self.X, self.W, state=self.state, Y=self.Y)
+    def fwd(self, binding, ws=None):
+        binding.halo_linear_fwd(self.desc, self.X, self.W, state=self.state, Y=self.Y, workspace=ws)
 
     def bwd(self, binding, ws):
         binding.halo_linear_bwd(self.desc, self.E, self.state, workspace=ws, EX=self.EX, G=self.G)
@@ -265,9 +266,9 @@ def oracle_slice(cfg, which_list, tokens):
         hb = (tokens & -tokens) if cfg.level >= 2 else 0
         Xr, Wr, Er = (orc.bf16_bits_to_real(t[k]) for k in ("X", "W", "E"))
         c0 = time.perf_counter()
-        f = orc.forward(Xr, Wr, cfg.level, hm)
-        orc.backward_input(Er, f["Wq"], f["s_w"], cfg.level, hm, hb)
-        orc.backward_weight(Er, f["Xq"], f["s_x"], cfg.level, hm)
+        f = orc.forward(Xr, Wr, cfg.level, hm, per_tensor=cfg.per_tensor)
+        orc.backward_input(Er, f["Wq"], f["s_w"], cfg.level, hm, hb, per_tensor=cfg.per_tensor)
+        orc.backward_weight(Er, f["Xq"], f["s_x"], cfg.level, hm, per_tensor=cfg.per_tensor)
         secs += time.perf_counter() - c0
         ops += 6.0 * tokens * lin.n * lin.m
     return secs, ops
@@ -281,11 +282,12 @@ def run_single(key, args, dev, copy_gbs, with_kernels, with_oracle):
     ws = torch.empty((max(L.ws_bytes, 1),), dtype=torch.uint8, device=dev)
 
     def step():
-        L.fwd(binding)
+        L.fwd(binding, ws if cfg.per_tensor else None)
         L.bwd(binding, ws)
     ms = time_steps(step, args.steps, args.warmup)
-    rec = dict(workload="%s: tokens %d, linear %dx%d (n x m), HALO-%d, INT8, bf16 in/out, fwd + both bwd products"
-                        % (key, L.b, L.n, L.m, L.level),
+    with_kernels = with_kernels and not cfg.per_tensor       # the per-kernel loops time the per-row entry points
+    rec = dict(workload="%s: tokens %d, linear %dx%d (n x m), HALO-%d, INT8%s, bf16 in/out, fwd + both bwd products"
+                        % (key, L.b, L.n, L.m, L.level, ", one scale per tensor" if cfg.per_tensor else ""),
                b=L.b, m=L.m, n=L.n, level=L.level, had_block_m=L.hm, had_block_b=L.hb, ops_per_step=L.ops,
                ms_per_step=ms, value=L.ops / (ms * 1e-3) / 1e12, unit="TOPS")
     kernels = None

@@ -124,6 +124,7 @@ class LayerConfig:
     backward: bool
     seed: int = 0
     kronecker: bool = False       # in-feature widths of the form 2^n * 28 get one block of the whole width
+    per_tensor: bool = False      # one scale per tensor (the paper's own quantiser) instead of one per row
 
     def had_block_m(self, m: int) -> int:
         """Right-hand Hadamard block: the largest power of two dividing m, at most 4096 (block-diagonal when that is
@@ -169,6 +170,9 @@ CONFIGS: Dict[str, LayerConfig] = {
     # The shape of c3 with the paper's Kronecker rotation H_512 (x) H_28 over K = 14336 in place of the block-diagonal one.
     "c6": LayerConfig("c6", 4096, (LinearShape("down", 4096, 14336),), level=2,
                       outlier_frac=0.001, backward=True, seed=6, kronecker=True),
+    # The shape of c2 with the paper's own quantiser: one scale per tensor.
+    "c7": LayerConfig("c7", 2048, (LinearShape("proj", 4096, 4096),), level=1,
+                      outlier_frac=0.001, backward=True, seed=7, per_tensor=True),
 }
 
 

@@ -242,3 +242,4 @@ def test_inputs_are_deterministic_and_shaped():
     assert inputs.CONFIGS["c2"].gemm_ops() == 6 * 2048 * 4096 * 4096
     assert inputs.CONFIGS["c3"].had_block_m(14336) == 2048
     assert inputs.CONFIGS["c6"].had_block_m(14336) == 14336 and inputs.CONFIGS["c6"].had_block_m(4096) == 4096
+    assert inputs.CONFIGS["c7"].per_tensor and not inputs.CONFIGS["c2"].per_tensor

@@ -58,6 +58,15 @@ def test_per_tensor_layers_all_levels(b, m, n, level):
     run_per_tensor(b, m, n, level, b + m + n)
 
 
+def test_config_c7_full_size_per_tensor():
+    """Config c7: the shape of c2 (tokens 2048, 4096 x 4096, HALO-1) with one scale per tensor, compared in full; and a
+    level-2 layer large enough for the product's epilogue to run the low left-hand strides with the tensor scale."""
+    cfg = inputs.CONFIGS["c7"]
+    assert cfg.per_tensor
+    run_per_tensor(cfg.tokens, 4096, 4096, cfg.level, cfg.seed * 1000)
+    run_per_tensor(1024, 2048, 512, 2, 11)
+
+
 def test_per_tensor_bf16_and_quantisation_error_of_both_modes_on_config_c1():
     """bf16 outputs; and on config c1's data (plus a heavy-tailed E) the error of each mode against the fp64 products:
     the per-row mode must be the more accurate one for the backward product fed by outlier-laden errors."""
