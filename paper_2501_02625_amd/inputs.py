@@ -34,6 +34,7 @@ __all__ = [
     "make_activations",
     "make_weights",
     "make_errors",
+    "make_adapters",
     "LinearShape",
     "LayerConfig",
     "CONFIGS",
@@ -105,6 +106,22 @@ def make_errors(rows: int, cols: int, seed: int) -> np.ndarray:
     return out
 
 
+ADAPTER_V_STD = 0.01
+
+
+def make_adapters(rank: int, n: int, m: int, seed: int) -> Tuple[np.ndarray, np.ndarray]:
+    """LoRA adapters of a linear with W [n, m], as bf16 bits: U [rank, m] and V [n, rank]  (Y = X W^T + (X U^T) V^T).
+
+    U is drawn as LoRA initialises its down-projection, uniform in +-1/sqrt(m).  V starts at zero in LoRA; a few
+    steps into fine-tuning it is small and dense, which is what is drawn here: N(0, 0.01^2).
+    """
+    g = _rng(seed, 3)
+    bound = np.float32(1.0 / np.sqrt(float(m)))
+    u = (g.random((rank, m), dtype=np.float32) * np.float32(2.0) - np.float32(1.0)) * bound
+    v = g.standard_normal((n, rank), dtype=np.float32) * np.float32(ADAPTER_V_STD)
+    return f32_to_bf16_bits(u), f32_to_bf16_bits(v)
+
+
 @dataclass(frozen=True)
 class LinearShape:
     """One linear layer: W is [n, m]; it maps b x m inputs to b x n outputs."""
@@ -125,6 +142,7 @@ class LayerConfig:
     seed: int = 0
     kronecker: bool = False       # in-feature widths of the form 2^n * 28 get one block of the whole width
     per_tensor: bool = False      # one scale per tensor (the paper's own quantiser) instead of one per row
+    peft_rank: int = 0            # > 0: HALO-PEFT, frozen quantised weight + LoRA adapters of this rank
 
     def had_block_m(self, m: int) -> int:
         """Right-hand Hadamard block: the largest power of two dividing m, at most 4096 (block-diagonal when that is
@@ -141,6 +159,9 @@ class LayerConfig:
 
     def gemm_ops(self) -> int:
         per = 2 * self.tokens * sum(l.n * l.m for l in self.linears)
+        if self.peft_rank:
+            # F and E on the frozen weight (no G), plus the six low-rank products of the adapters
+            return per * 2 + 6 * self.tokens * self.peft_rank * sum(l.n + l.m for l in self.linears)
         return per * (3 if self.backward else 1)
 
 
@@ -173,6 +194,10 @@ CONFIGS: Dict[str, LayerConfig] = {
     # The shape of c2 with the paper's own quantiser: one scale per tensor.
     "c7": LayerConfig("c7", 2048, (LinearShape("proj", 4096, 4096),), level=1,
                       outlier_frac=0.001, backward=True, seed=7, per_tensor=True),
+    # HALO-PEFT (Appendix "LoRA-style Linear Module and HALO for PEFT"): frozen quantised 4096 x 4096 weight, rank-16
+    # adapters (the rank of the paper's PEFT table), level-2 forms of F and E, 4096 tokens.
+    "c8": LayerConfig("c8", 4096, (LinearShape("proj", 4096, 4096),), level=2,
+                      outlier_frac=0.001, backward=True, seed=8, peft_rank=16),
 }
 
 
@@ -191,4 +216,6 @@ def make_linear_inputs(cfg: LayerConfig, which: int = 0, *, tokens: int | None =
     }
     if cfg.backward if need_error is None else need_error:
         out["E"] = make_errors(b, lin.n, sub)
+    if cfg.peft_rank:
+        out["U"], out["V"] = make_adapters(cfg.peft_rank, lin.n, lin.m, sub)
     return out
