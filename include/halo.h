@@ -304,6 +304,43 @@ halo_status halo_linear_bwd(const halo_linear_desc* desc, const void* E, const i
                             const float* s_x, const int8_t* Wq, const float* s_w, void* EX, void* G,
                             void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---------------------------------------------------------------------------------------------
+ * HALO-PEFT: a LoRA-style module on a frozen, quantised weight.  (Section 3.3 "Parameter Efficient Fine Tuning";
+ * Appendix "LoRA-style Linear Module and HALO for PEFT".)
+ *
+ *   Y   = (XH)_Q (WH)_Q^T  +  (X U^T) V^T
+ *   E_X = H^T (H E_Y)_Q (WH)_Q H^T  +  (E_Y V) U            (the forms of desc->level; the paper uses level 2)
+ *   G_V = E_Y^T (X U^T)        G_U = (V^T E_Y^T) X           (adapter gradients; there is no G for the frozen W)
+ *
+ * The frozen weight is rotated and quantised ONCE, before fine-tuning, with
+ * halo_hadamard_quant(W, HALO_BF16, n, m, m, HALO_QUANT_ROWS, had_block_m, 0, NULL, Wq, m, s_w, ...); Wq int8 [n x m] and
+ * s_w fp32 [n] are inputs here.  U bf16 [rank x m] (ld m) and V bf16 [n x rank] (ld rank) are the adapters; any LoRA
+ * scaling factor is folded into V by the caller.  The low-rank products are the "high precision" part: bf16 inputs,
+ * fp32 accumulation, the intermediates T = X U^T and S = E_Y V kept in fp32, and the low-rank term is added to the fp32
+ * value of the quantised branch before the single rounding to desc->out_dt.  (For E_X it is added in the rotated
+ * domain, as (H S)(U H), and un-rotated together with the product: equal to S U up to fp32 rounding.)
+ *
+ *   rank          a multiple of 8, at most 64.
+ *   desc          as for halo_linear_*; scale_mode must be HALO_SCALE_PER_ROW; m and n multiples of 64.
+ *   T             fp32 [b x rank] (dense): written by the forward pass, read by the backward pass (for G_V).
+ *   G_U, G_V      fp32 [rank x m] and [n x rank], dense.
+ *   workspace     halo_peft_workspace_bytes(desc, rank) bytes of device memory, 16-byte aligned; nothing in it is
+ *                 carried from the forward to the backward call.
+ * All pointers are device pointers, 16-byte aligned.  Errors as elsewhere: HALO_EINVAL (null / bad enum), HALO_ESHAPE,
+ * HALO_EALIGN, HALO_EWORKSPACE, HALO_EUNSUPPORTED (per-tensor scales, rank > 64), HALO_EHIP.
+ */
+size_t halo_peft_workspace_bytes(const halo_linear_desc* desc, int32_t rank);
+
+halo_status halo_peft_fwd(const halo_linear_desc* desc, int32_t rank, const void* X, const int8_t* Wq, const float* s_w,
+                          const void* U, const void* V, void* Y, float* T, void* workspace, size_t workspace_bytes,
+                          void* stream);
+
+/* EX [b x m] in desc->out_dt; any of EX, GU, GV may be NULL to skip it (not all three).  X is read for G_U only, T for
+ * G_V only, Wq / s_w / U for E_X only. */
+halo_status halo_peft_bwd(const halo_linear_desc* desc, int32_t rank, const void* E, const void* X, const float* T,
+                          const int8_t* Wq, const float* s_w, const void* U, const void* V, void* EX, float* GU, float* GV,
+                          void* workspace, size_t workspace_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -13,7 +13,7 @@ INCLUDE = os.path.join(ROOT, "include")
 LIB_PATH = os.path.join(PKG_DIR, "libhalo.so")
 BUILD_DIR = os.path.join(PKG_DIR, "_build")
 
-SOURCES = ["halo_api.hip", "row_transform.hip", "col_ops.hip", "gemm_i8.hip", "gemm_mx6.hip", "row_kron.hip"]
+SOURCES = ["halo_api.hip", "row_transform.hip", "col_ops.hip", "gemm_i8.hip", "gemm_mx6.hip", "row_kron.hip", "lowrank.hip"]
 
 # -ffp-contract=off: every fp32 add/mul of the rotation and the quantiser is rounded on its own, which is
 # what makes the INT8 codes reproducible bit for bit.  Packed fp32 instructions are switched off.
@@ -51,7 +51,7 @@ def build(verbose: bool = False) -> str:
         src, obj = pair
         return _run([hipcc, *HIPCC_FLAGS, "-c", os.path.join(CSRC, src), "-o", obj])
 
-    with ThreadPoolExecutor(max_workers=min(5, len(SOURCES))) as pool:
+    with ThreadPoolExecutor(max_workers=min(7, len(SOURCES))) as pool:
         logs = list(pool.map(compile_one, zip(SOURCES, objs)))
     logs.append(_run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB_PATH]))
     if verbose:

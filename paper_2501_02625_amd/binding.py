@@ -33,6 +33,7 @@ EXPORTED_SYMBOLS = (
     "halo_mx6_quant", "halo_gemm_mx6",
     "halo_dequant_unrotate_workspace_bytes", "halo_dequant_unrotate",
     "halo_linear_workspace_bytes", "halo_linear_fwd", "halo_linear_bwd",
+    "halo_peft_workspace_bytes", "halo_peft_fwd", "halo_peft_bwd",
 )
 
 
@@ -114,6 +115,12 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.halo_linear_fwd.argtypes = [c.POINTER(LinearDesc), vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.halo_linear_bwd.restype = c.c_int
     lib.halo_linear_bwd.argtypes = [c.POINTER(LinearDesc), vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.halo_peft_workspace_bytes.restype = sz
+    lib.halo_peft_workspace_bytes.argtypes = [c.POINTER(LinearDesc), i32]
+    lib.halo_peft_fwd.restype = c.c_int
+    lib.halo_peft_fwd.argtypes = [c.POINTER(LinearDesc), i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.halo_peft_bwd.restype = c.c_int
+    lib.halo_peft_bwd.argtypes = [c.POINTER(LinearDesc), i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     if path == _build.LIB_PATH:
         _lib = lib
     return lib
@@ -428,3 +435,55 @@ def halo_linear_bwd(desc: LinearDesc, E: torch.Tensor, state: LinearState, *, wa
                              _ptr(workspace), workspace.numel(), _stream())
     _check(st, "halo_linear_bwd")
     return (EX if want_ex else None), (G if want_g else None)
+
+
+def halo_peft_workspace_bytes(desc: LinearDesc, rank: int) -> int:
+    return int(load_library().halo_peft_workspace_bytes(ctypes.byref(desc), int(rank)))
+
+
+def halo_peft_fwd(desc: LinearDesc, X: torch.Tensor, Wq: torch.Tensor, s_w: torch.Tensor, U: torch.Tensor,
+                  V: torch.Tensor, *, workspace: Optional[torch.Tensor] = None, Y: Optional[torch.Tensor] = None,
+                  T: Optional[torch.Tensor] = None):
+    """Forward pass of the LoRA-style module on a frozen quantised weight; returns (Y, T = X U^T in fp32)."""
+    lib = load_library()
+    _need_cuda(X, Wq, s_w, U, V, workspace, Y, T)
+    rank = U.shape[0]
+    assert X.dtype == torch.bfloat16 and U.dtype == torch.bfloat16 and V.dtype == torch.bfloat16
+    assert X.is_contiguous() and U.is_contiguous() and V.is_contiguous() and Wq.is_contiguous()
+    assert tuple(V.shape) == (desc.n, rank) and tuple(U.shape) == (rank, desc.m)
+    odt = torch.bfloat16 if desc.out_dt == HALO_BF16 else torch.float32
+    if Y is None:
+        Y = torch.empty((desc.b, desc.n), dtype=odt, device=X.device)
+    if T is None:
+        T = torch.empty((desc.b, rank), dtype=torch.float32, device=X.device)
+    if workspace is None:
+        workspace = torch.empty((max(halo_peft_workspace_bytes(desc, rank), 1),), dtype=torch.uint8, device=X.device)
+    st = lib.halo_peft_fwd(ctypes.byref(desc), rank, _ptr(X), _ptr(Wq), _ptr(s_w), _ptr(U), _ptr(V), _ptr(Y), _ptr(T),
+                           _ptr(workspace), workspace.numel(), _stream())
+    _check(st, "halo_peft_fwd")
+    return Y, T
+
+
+def halo_peft_bwd(desc: LinearDesc, E: torch.Tensor, X: torch.Tensor, T: torch.Tensor, Wq: torch.Tensor,
+                  s_w: torch.Tensor, U: torch.Tensor, V: torch.Tensor, *, want_ex: bool = True, want_gu: bool = True,
+                  want_gv: bool = True, workspace: Optional[torch.Tensor] = None, EX: Optional[torch.Tensor] = None,
+                  GU: Optional[torch.Tensor] = None, GV: Optional[torch.Tensor] = None):
+    """Backward pass of the module; returns (E_X, G_U [rank x m] fp32, G_V [n x rank] fp32), None where not wanted."""
+    lib = load_library()
+    _need_cuda(E, X, T, Wq, s_w, U, V, workspace, EX, GU, GV)
+    rank = U.shape[0]
+    assert E.dtype == torch.bfloat16 and E.is_contiguous()
+    odt = torch.bfloat16 if desc.out_dt == HALO_BF16 else torch.float32
+    if want_ex and EX is None:
+        EX = torch.empty((desc.b, desc.m), dtype=odt, device=E.device)
+    if want_gu and GU is None:
+        GU = torch.empty((rank, desc.m), dtype=torch.float32, device=E.device)
+    if want_gv and GV is None:
+        GV = torch.empty((desc.n, rank), dtype=torch.float32, device=E.device)
+    if workspace is None:
+        workspace = torch.empty((max(halo_peft_workspace_bytes(desc, rank), 1),), dtype=torch.uint8, device=E.device)
+    st = lib.halo_peft_bwd(ctypes.byref(desc), rank, _ptr(E), _ptr(X), _ptr(T), _ptr(Wq), _ptr(s_w), _ptr(U), _ptr(V),
+                           _ptr(EX) if want_ex else None, _ptr(GU) if want_gu else None, _ptr(GV) if want_gv else None,
+                           _ptr(workspace), workspace.numel(), _stream())
+    _check(st, "halo_peft_bwd")
+    return (EX if want_ex else None), (GU if want_gu else None), (GV if want_gv else None)

@@ -60,7 +60,7 @@ typedef int v2i __attribute__((ext_vector_type(2)));
 template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, bool TRANSB, int NS, bool TR = false>
 struct GemmCfg {
     static constexpr bool IS_TR = TR;
-    static constexpr int BN_ = BN;
+    static constexpr int BM_ = BM, BN_ = BN;
     static constexpr int WAVES_M_ = WAVES_M, WAVES_N_ = WAVES_N;
     static constexpr int NT = 64 * WAVES_M * WAVES_N;
     // tile-rows per group of the workgroup->tile map (4 measured best of 2/4/8/16 on the Llama-shaped products)
@@ -270,7 +270,8 @@ __device__ __forceinline__ void mma_stage(const unsigned char* sa, const unsigne
 // covered rows.  Only the owning wavefront touches its region, so after the first barrier the wavefront only has to
 // order its own LDS writes and reads (the lanes of a wavefront run in lockstep; the wavefront-scope fences keep the
 // compiler from moving the accesses across the slab boundaries).
-template <class Cfg>
+// PRE: the accumulator registers already hold the fp32 values to store, as bit patterns (lowrank_prepare).
+template <class Cfg, bool PRE = false>
 __device__ __forceinline__ void epilogue(const GemmArgs& a, int64_t m0, int64_t n0, int wave, int wave_m, int wave_n,
                                          int lane, const v16i (&acc)[Cfg::TM][Cfg::TN], unsigned char* smem) {
     constexpr int WN = Cfg::WN, PITCH = Cfg::EPI_PITCH;
@@ -284,7 +285,7 @@ __device__ __forceinline__ void epilogue(const GemmArgs& a, int64_t m0, int64_t 
     const int64_t col = n0 + wave_n * WN + cc;
     const bool col_any = col < a.N, col_all = col + 4 <= a.N;
     float cs[4] = {1.0f, 1.0f, 1.0f, 1.0f};
-    if (a.C && a.col_scale) {
+    if (!PRE && a.C && a.col_scale) {
 #pragma unroll
         for (int e = 0; e < 4; ++e)
             if (col + e < a.N) cs[e] = a.col_scale[col + e];
@@ -307,7 +308,7 @@ __device__ __forceinline__ void epilogue(const GemmArgs& a, int64_t m0, int64_t 
             const int64_t row = m0 + wave_m * Cfg::WM + i * 32 + rr;
             if (row >= a.M || !col_any) continue;
             const int vv[4] = {v.x, v.y, v.z, v.w};
-            if (a.acc_out) {
+            if (!PRE && a.acc_out) {
                 int32_t* dst = a.acc_out + row * a.ld_acc + col;
                 if (col_all) {
                     *reinterpret_cast<int4*>(dst) = v;
@@ -318,10 +319,15 @@ __device__ __forceinline__ void epilogue(const GemmArgs& a, int64_t m0, int64_t 
                 }
             }
             if (a.C) {
-                const float rs = a.row_scale ? a.row_scale[row] : 1.0f;
                 float f[4];
+                if constexpr (PRE) {
 #pragma unroll
-                for (int e = 0; e < 4; ++e) f[e] = ((float)vv[e] * rs) * cs[e];
+                    for (int e = 0; e < 4; ++e) f[e] = __int_as_float(vv[e]);
+                } else {
+                    const float rs = a.row_scale ? a.row_scale[row] : 1.0f;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) f[e] = ((float)vv[e] * rs) * cs[e];
+                }
                 if (a.c_is_f32) {
                     float* dst = reinterpret_cast<float*>(a.C) + row * a.ldc + col;
                     if (col_all) {
@@ -357,7 +363,7 @@ __device__ __forceinline__ void epilogue(const GemmArgs& a, int64_t m0, int64_t 
 // staging of the store (each wavefront reads its own slab and its partner's).  The columns are independent, so one
 // 32-column tile of the wavefront is taken through all of this at a time (64 live values per lane).  No normalisation:
 // the 1/sqrt(block) of the rotation is applied after its last stride, by whoever runs it.
-template <class Cfg>
+template <class Cfg, bool PRE = false>
 __device__ __forceinline__ void epilogue_left8(const GemmArgs& a, int64_t m0, int64_t n0, int wave, int wave_m, int wave_n,
                                                int lane, const v16i (&acc)[Cfg::TM][Cfg::TN], unsigned char* smem) {
     static_assert(Cfg::TM == 4 && Cfg::WAVES_M_ == 2, "256-row tiles, two wavefronts down the rows");
@@ -371,8 +377,10 @@ __device__ __forceinline__ void epilogue_left8(const GemmArgs& a, int64_t m0, in
     const float* partner = reinterpret_cast<const float*>(smem + 1024) + (wave ^ Cfg::WAVES_N_) * 2 * SLAB;
     __syncthreads();                       // every wavefront is done with the operand stages
     const int tid = wave * 64 + lane;
-    if (tid < 256) s_scale[tid] = a.row_scale ? a.row_scale[m0 + tid] : 1.0f;      // M is a multiple of 256
-    __syncthreads();
+    if constexpr (!PRE) {
+        if (tid < 256) s_scale[tid] = a.row_scale ? a.row_scale[m0 + tid] : 1.0f;  // M is a multiple of 256
+        __syncthreads();
+    }
     const float post = a.post_scale ? *a.post_scale : 1.0f;                          // x * 1.0f is x
     const float sgn = half ? -1.0f : 1.0f;                   // lower half: a + b;  upper half: a - b = partner - own
     const float sgn_w = wave_m ? -1.0f : 1.0f;               // the same for the two wavefronts of stride 128
@@ -386,8 +394,12 @@ __device__ __forceinline__ void epilogue_left8(const GemmArgs& a, int64_t m0, in
         for (int i = 0; i < TM; ++i)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const float rs = s_scale[wave_m * 128 + i * 32 + 8 * (r >> 2) + 4 * half + (r & 3)];
-                f[i][r] = ((float)acc[i][j][r] * rs) * post;
+                if constexpr (PRE) {
+                    f[i][r] = __int_as_float(acc[i][j][r]);
+                } else {
+                    const float rs = s_scale[wave_m * 128 + i * 32 + 8 * (r >> 2) + 4 * half + (r & 3)];
+                    f[i][r] = ((float)acc[i][j][r] * rs) * post;
+                }
             }
         // strides 1, 2, (4), 8, 16: bits 0, 1, 2, 3 of r; stride 4 across the lane halves in between
 #pragma unroll
@@ -467,11 +479,81 @@ __device__ __forceinline__ void epilogue_left8(const GemmArgs& a, int64_t m0, in
     }
 }
 
+// Low-rank side product (a LoRA branch next to the quantised product): turns the int32 accumulators, in place, into the
+// fp32 values
+//   ((float(acc) * row_scale[row]) * col_scale[col]) * post_scale  +  sum_k lr_a[row, k] * lr_b[k, col],
+// the first part rounded exactly as the plain epilogues round it, the sum added by fp32 matrix instructions
+// (v_mfma_f32_32x32x2_f32, whose result layout is that of the int8 instruction: lane l supplies A[row l % 32][k l / 32]
+// and B[k l / 32][col l % 32]) with the scaled accumulator as their addend.  The registers then hold float bit patterns
+// and the PRE variants of the epilogues take over.  Sixteen ranks at a time: their operands are fetched in one batch.
+template <class Cfg>
+__device__ __forceinline__ void lowrank_prepare(const GemmArgs& a, int64_t m0, int64_t n0, int wave, int wave_m, int wave_n,
+                                                int lane, v16i (&acc)[Cfg::TM][Cfg::TN], unsigned char* smem) {
+    constexpr int TM = Cfg::TM, TN = Cfg::TN;
+    static_assert(Cfg::BM_ * 4 <= 1024, "row scales fit below the staging regions of the left-hand epilogue");
+    typedef float v16f __attribute__((ext_vector_type(16)));
+    const int lrow = lane & 31, half = lane >> 5;
+    float* s_scale = reinterpret_cast<float*>(smem);
+    __syncthreads();                       // every wavefront is done with the operand stages
+    for (int t = wave * 64 + lane; t < Cfg::BM_; t += Cfg::NT) {
+        const int64_t row = m0 + t;
+        s_scale[t] = (a.row_scale && row < a.M) ? a.row_scale[row] : 1.0f;
+    }
+    __syncthreads();
+    const float post = a.post_scale ? *a.post_scale : 1.0f;                          // x * 1.0f is x
+    float cs[TN];
+    int64_t colj[TN];
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        colj[j] = n0 + wave_n * Cfg::WN + j * 32 + lrow;
+        cs[j] = (a.col_scale && colj[j] < a.N) ? a.col_scale[colj[j]] : 1.0f;
+    }
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const float rs = s_scale[wave_m * Cfg::WM + i * 32 + 8 * (r >> 2) + 4 * half + (r & 3)];
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                acc[i][j][r] = __float_as_int((((float)acc[i][j][r] * rs) * cs[j]) * post);
+        }
+    for (int c0 = 0; c0 < a.lr_rank; c0 += 16) {
+        float av[TM][8], bv[TN][8];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int64_t row = m0 + wave_m * Cfg::WM + i * 32 + lrow;
+#pragma unroll
+            for (int kk = 0; kk < 8; ++kk) {
+                const int k = c0 + 2 * kk + half;
+                av[i][kk] = (row < a.M && k < a.lr_rank) ? a.lr_a[row * a.lr_rank + k] : 0.0f;
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int kk = 0; kk < 8; ++kk) {
+                const int k = c0 + 2 * kk + half;
+                bv[j][kk] = (colj[j] < a.N && k < a.lr_rank) ? a.lr_b[(int64_t)k * a.ld_lrb + colj[j]] : 0.0f;
+            }
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                v16f f = __builtin_bit_cast(v16f, acc[i][j]);
+#pragma unroll
+                for (int kk = 0; kk < 8; ++kk)
+                    f = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i][kk], bv[j][kk], f, 0, 0, 0);
+                acc[i][j] = __builtin_bit_cast(v16i, f);
+            }
+    }
+}
+
 // ------------------------------------------------------------------------------------------------ dma main loop
 // Both operands go through the DMA ring.  K must be a multiple of BK (the DMA cannot zero-fill a K tail).
 // LEFT: this instance also carries the epilogue that runs the low strides of a left-hand rotation (its own instance, so
 // that the register spills of that epilogue stay out of the kernels that never take it).
-template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, bool TRANSB, int NS, bool LEFT = false>
+// LR: this instance also carries the low-rank side product (lowrank_prepare), again its own instance.
+template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, bool TRANSB, int NS, bool LEFT = false, bool LR = false>
 __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N)
 gemm_i8_dma_kernel(GemmArgs a, int tiles_m, int tiles_n, GemmArgs a2, int tiles_m2, int tiles_n2, unsigned blocks1) {
     using Cfg = GemmCfg<BM, BN, BK, WAVES_M, WAVES_N, TRANSB, NS, !TRANSB>;
@@ -584,6 +666,19 @@ gemm_i8_dma_kernel(GemmArgs a, int tiles_m, int tiles_n, GemmArgs a2, int tiles_
             }
         }
         asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+    }
+    if constexpr (LR) {
+        if (a.lr_rank > 0) {               // uniform over the workgroup
+            lowrank_prepare<Cfg>(a, m0, n0, wave, wave_m, wave_n, lane, acc, smem);
+            if constexpr (LEFT) {
+                if (a.left_stages != 0) {
+                    epilogue_left8<Cfg, true>(a, m0, n0, wave, wave_m, wave_n, lane, acc, smem);
+                    return;
+                }
+            }
+            epilogue<Cfg, true>(a, m0, n0, wave, wave_m, wave_n, lane, acc, smem);
+            return;
+        }
     }
     if constexpr (LEFT) {
         if (a.left_stages != 0) {          // uniform over the workgroup
@@ -765,24 +860,39 @@ hipError_t raise_lds_limit(Kern kern, int lds_bytes, std::once_flag* once, hipEr
     return *result;
 }
 
-template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, bool TRANSB, int NS, bool LEFT = false>
+template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, bool TRANSB, int NS, bool LEFT = false, bool LR = false>
 hipError_t launch_dma(const GemmArgs& a, hipStream_t s, const GemmArgs* a2 = nullptr) {
     using Cfg = GemmCfg<BM, BN, BK, WAVES_M, WAVES_N, TRANSB, NS, !TRANSB>;
     const bool wants_left = a.left_stages != 0 || (a2 && a2->left_stages != 0);
-    if constexpr (!LEFT && BM == 256 && WAVES_M == 2 && !TRANSB) {
+    const bool wants_lr = a.lr_rank != 0 || (a2 && a2->lr_rank != 0);
+    // The low-rank instances exist for the configurations the layer uses: K-contiguous B with 128-byte K steps or the
+    // small tile, K-strided B with 256x256 (which then also carries the left-hand epilogue) or the small tile.
+    constexpr bool kLeftShape = BM == 256 && WAVES_M == 2 && !TRANSB;
+    constexpr bool kLrShape = TRANSB ? (BK == 128 || BM == 128) : (BK == 64);
+    if constexpr (!LR && kLrShape) {
+        if (wants_lr) return launch_dma<BM, BN, BK, WAVES_M, WAVES_N, TRANSB, NS, kLeftShape, true>(a, s, a2);
+    }
+    if (wants_lr && !LR) return hipErrorInvalidValue;
+    if constexpr (!LEFT && !LR && kLeftShape) {
         if (wants_left) return launch_dma<BM, BN, BK, WAVES_M, WAVES_N, TRANSB, NS, true>(a, s, a2);
     }
     if (wants_left && !LEFT) return hipErrorInvalidValue;
+    auto lr_ok = [](const GemmArgs& g) {
+        if (g.lr_rank == 0) return true;
+        return g.lr_rank > 0 && g.lr_rank <= kMaxLowRank && g.lr_a && g.lr_b && g.ld_lrb >= g.N && g.C && !g.acc_out;
+    };
+    if (!lr_ok(a) || (a2 && !lr_ok(*a2))) return hipErrorInvalidValue;
     static std::once_flag once;
     static hipError_t attr_result = hipSuccess;
-    auto kern = gemm_i8_dma_kernel<BM, BN, BK, WAVES_M, WAVES_N, TRANSB, NS, LEFT>;
+    auto kern = gemm_i8_dma_kernel<BM, BN, BK, WAVES_M, WAVES_N, TRANSB, NS, LEFT, LR>;
     hipError_t e = raise_lds_limit(kern, Cfg::LDS_BYTES, &once, &attr_result);
     if (e != hipSuccess) return e;
     if (a.K % BK != 0 || (a2 && a2->K % BK != 0)) return hipErrorInvalidValue;
     // the epilogue that runs the low strides of a left-hand rotation: 256-row tiles that lie inside the matrix, fp32 out
     auto left_ok = [](const GemmArgs& g) {
         if (g.left_stages == 0) return true;
-        return g.left_stages == 8 && g.M % 256 == 0 && g.C && g.c_is_f32 && !g.acc_out && !g.col_scale && g.K > 0;
+        return g.left_stages == 8 && g.M % 256 == 0 && g.C && g.c_is_f32 && !g.acc_out && (!g.col_scale || g.lr_rank) &&
+               g.K > 0;
     };
     if (!left_ok(a) || (a2 && !left_ok(*a2))) return hipErrorInvalidValue;
     const int tiles_m = (int)((a.M + BM - 1) / BM), tiles_n = (int)((a.N + BN - 1) / BN);
@@ -802,7 +912,7 @@ hipError_t launch_staged(const GemmArgs& a, hipStream_t s) {
     using Cfg = GemmCfg<128, 128, 64, 2, 2, TRANSB, 2>;
     static std::once_flag once;
     static hipError_t attr_result = hipSuccess;
-    if (a.left_stages != 0) return hipErrorInvalidValue;
+    if (a.left_stages != 0 || a.lr_rank != 0) return hipErrorInvalidValue;
     auto kern = gemm_i8_staged_kernel<128, 128, 64, 2, 2, TRANSB>;
     hipError_t e = raise_lds_limit(kern, Cfg::LDS_BYTES, &once, &attr_result);
     if (e != hipSuccess) return e;

@@ -114,8 +114,10 @@ inline bool left_in_epilogue(int64_t b, int64_t n, int32_t hb) { return hb >= 25
 // The rest of that un-rotation: t [b x m] fp32 holds the product after the eight low left-hand strides.  Either one
 // kernel (top strides across the wavefronts of a workgroup, then each row's right-hand un-rotation), or the remaining
 // strides in place and then the row kernel (1/sqrt(left block), right-hand un-rotation, conversion).
+// first_stage: the left-hand strides below 2^first_stage have run already (8 after the GEMM epilogue that runs them, 0
+// after a plain epilogue).
 hipError_t finish_left_unrotation(float* t, int64_t b, int64_t m, int32_t hb, int32_t hm, void* out, halo_dtype odt,
-                                  hipStream_t s) {
+                                  hipStream_t s, int first_stage = 8) {
     RowArgs r{};
     r.in = t; r.ld_in = m; r.rows = b; r.cols = m; r.out = out; r.ld_out = m;
     r.in_mul = (float)(1.0 / sqrt((double)hb));
@@ -123,15 +125,53 @@ hipError_t finish_left_unrotation(float* t, int64_t b, int64_t m, int32_t hb, in
     const OutKind ok = odt == HALO_BF16 ? OUT_BF16 : OUT_F32;
     // up to four top strides left and a right-hand block of 512 .. 2048: one kernel does the rest
     const int top = ilog2_exact(hb) - 8;
-    if (r.kron_m == 0 && row_left_top_ok(b, m, r.log_block, top)) {
+    if (first_stage == 8 && r.kron_m == 0 && row_left_top_ok(b, m, r.log_block, top)) {
         r.left_top = top;
         return launch_row_left_top(r, ok, s);
     }
     ColFwhtArgs c{t, IN_F32, m, t, OUT_F32, m, t, m, b, m, ilog2_exact(hb)};
-    c.first_stage = 8; c.skip_norm = 1;
+    c.first_stage = first_stage; c.skip_norm = 1;
     hipError_t e = launch_col_fwht(c, s);
     if (e != hipSuccess) return e;
     return launch_row_transform(r, IN_F32, ok, s);
+}
+
+// Scratch of the HALO-PEFT entry points (one layout for both directions).
+struct PeftWorkspace {
+    size_t xq, s_x, vt, eq, s_e, c32, f32, s, sp, up, part, total;
+};
+
+PeftWorkspace peft_layout(const halo_linear_desc* d, int32_t rank) {
+    PeftWorkspace w{};
+    size_t off = 0;
+    const size_t b = (size_t)d->b, m = (size_t)d->m, n = (size_t)d->n, r = (size_t)rank;
+    w.xq = off;   off += round256(b * m);
+    w.s_x = off;  off += round256(b * 4);
+    w.vt = off;   off += round256(r * n * 4);
+    w.eq = off;   off += round256(b * n);
+    w.s_e = off;  off += round256(b * 4);
+    w.c32 = off;  off += round256(b * m * 4);       // the E product in fp32, before its un-rotation
+    w.f32 = off;
+    if (d->level >= 2) off += round256(b * (m > n ? m : n) * 4);
+    w.s = off;    off += round256(b * r * 4);
+    w.sp = off;   off += round256(b * r * 4);
+    w.up = off;   off += round256(r * m * 4);
+    const size_t pn = lr_grad_workspace_floats(d->b, d->n, rank), pm = lr_grad_workspace_floats(d->b, d->m, rank);
+    w.part = off; off += round256((pn > pm ? pn : pm) * 4);
+    w.total = off;
+    return w;
+}
+
+halo_status resolve_peft(const halo_linear_desc* d, int32_t rank, int32_t* hm, int32_t* hb) {
+    halo_status st = resolve_desc(d, hm, hb);
+    if (st != HALO_OK) return st;
+    if (d->scale_mode != HALO_SCALE_PER_ROW) return HALO_EUNSUPPORTED;
+    if (rank <= 0) return HALO_EINVAL;
+    if (rank % 8) return HALO_ESHAPE;
+    if (rank > kMaxLowRank) return HALO_EUNSUPPORTED;
+    if (d->m % 64 || d->n % 64) return HALO_ESHAPE;       // both are reduction lengths of a K-step GEMM
+    if (!lr_row_fwht_shape_ok(d->m, *hm)) return HALO_EUNSUPPORTED;
+    return HALO_OK;
 }
 
 }  // namespace
@@ -668,6 +708,111 @@ halo_status halo_linear_bwd(const halo_linear_desc* desc, const void* E, const i
         if (st != HALO_OK) return st;
     }
     return HALO_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
+size_t halo_peft_workspace_bytes(const halo_linear_desc* desc, int32_t rank) {
+    int32_t hm, hb;
+    if (resolve_peft(desc, rank, &hm, &hb) != HALO_OK) return 0;
+    return peft_layout(desc, rank).total;
+}
+
+halo_status halo_peft_fwd(const halo_linear_desc* desc, int32_t rank, const void* X, const int8_t* Wq, const float* s_w,
+                          const void* U, const void* V, void* Y, float* T, void* workspace, size_t workspace_bytes,
+                          void* stream) {
+    int32_t hm, hb;
+    halo_status st = resolve_peft(desc, rank, &hm, &hb);
+    if (st != HALO_OK) return st;
+    if (!X || !Wq || !s_w || !U || !V || !Y || !T) return HALO_EINVAL;
+    const int64_t b = desc->b, m = desc->m, n = desc->n;
+    if (b == 0 || m == 0 || n == 0) return HALO_OK;
+    const PeftWorkspace L = peft_layout(desc, rank);
+    if (!workspace || workspace_bytes < L.total) return HALO_EWORKSPACE;
+    if (!aligned16(workspace) || !aligned16(X) || !aligned16(Wq) || !aligned16(U) || !aligned16(V) || !aligned16(Y) ||
+        !aligned16(T))
+        return HALO_EALIGN;
+    unsigned char* ws = reinterpret_cast<unsigned char*>(workspace);
+    int8_t* Xq = reinterpret_cast<int8_t*>(ws + L.xq);
+    float* s_x = reinterpret_cast<float*>(ws + L.s_x);
+    float* vt = reinterpret_cast<float*>(ws + L.vt);
+    hipStream_t hs = reinterpret_cast<hipStream_t>(stream);
+
+    st = halo_hadamard_quant(X, HALO_BF16, b, m, m, HALO_QUANT_ROWS, hm, 0, nullptr, Xq, m, s_x, nullptr, 0, stream);
+    if (st != HALO_OK) return st;
+    if (launch_lr_down(X, m, U, 0, m, T, b, m, rank, hs) != hipSuccess) return HALO_EHIP;
+    if (launch_lr_transpose(V, vt, n, rank, hs) != hipSuccess) return HALO_EHIP;
+    GemmArgs g{Xq, m, Wq, m, 1, b, n, m, s_x, s_w, Y, desc->out_dt == HALO_F32 ? 1 : 0, n, nullptr, 0, HALO_GEMM_AUTO};
+    g.lr_rank = rank; g.lr_a = T; g.lr_b = vt; g.ld_lrb = n;
+    return from_hip(launch_gemm_i8(g, hs));
+}
+
+halo_status halo_peft_bwd(const halo_linear_desc* desc, int32_t rank, const void* E, const void* X, const float* T,
+                          const int8_t* Wq, const float* s_w, const void* U, const void* V, void* EX, float* GU, float* GV,
+                          void* workspace, size_t workspace_bytes, void* stream) {
+    int32_t hm, hb;
+    halo_status st = resolve_peft(desc, rank, &hm, &hb);
+    if (st != HALO_OK) return st;
+    if (!E || (!EX && !GU && !GV)) return HALO_EINVAL;
+    if ((EX || GU) && !V) return HALO_EINVAL;
+    if (EX && (!Wq || !s_w || !U)) return HALO_EINVAL;
+    if (GU && !X) return HALO_EINVAL;
+    if (GV && !T) return HALO_EINVAL;
+    const int64_t b = desc->b, m = desc->m, n = desc->n;
+    if (b == 0 || m == 0 || n == 0) return HALO_OK;
+    const PeftWorkspace L = peft_layout(desc, rank);
+    if (!workspace || workspace_bytes < L.total) return HALO_EWORKSPACE;
+    if (!aligned16(workspace) || !aligned16(E) || (X && !aligned16(X)) || (T && !aligned16(T)) || (Wq && !aligned16(Wq)) ||
+        (U && !aligned16(U)) || (V && !aligned16(V)) || (EX && !aligned16(EX)) || (GU && !aligned16(GU)) ||
+        (GV && !aligned16(GV)))
+        return HALO_EALIGN;
+    const halo_dtype odt = (halo_dtype)desc->out_dt;
+    const int level = desc->level;
+    unsigned char* ws = reinterpret_cast<unsigned char*>(workspace);
+    float* vt = reinterpret_cast<float*>(ws + L.vt);
+    int8_t* Eq = reinterpret_cast<int8_t*>(ws + L.eq);
+    float* s_e = reinterpret_cast<float*>(ws + L.s_e);
+    float* c32 = reinterpret_cast<float*>(ws + L.c32);
+    float* f32 = reinterpret_cast<float*>(ws + L.f32);
+    float* S = reinterpret_cast<float*>(ws + L.s);
+    float* Sp = reinterpret_cast<float*>(ws + L.sp);
+    float* Up = reinterpret_cast<float*>(ws + L.up);
+    float* part = reinterpret_cast<float*>(ws + L.part);
+    hipStream_t hs = reinterpret_cast<hipStream_t>(stream);
+
+    // ---- the thin products: S = E V, G_V = E^T T, G_U = S^T X
+    if (EX || GU) {
+        if (launch_lr_transpose(V, vt, n, rank, hs) != hipSuccess) return HALO_EHIP;
+        if (launch_lr_down(E, n, vt, 1, n, S, b, n, rank, hs) != hipSuccess) return HALO_EHIP;
+    }
+    if (GV && launch_lr_grad(E, n, T, GV, 0, part, b, n, rank, hs) != hipSuccess) return HALO_EHIP;
+    if (GU && launch_lr_grad(X, m, S, GU, 1, part, b, m, rank, hs) != hipSuccess) return HALO_EHIP;
+    if (!EX) return HALO_OK;
+
+    // ---- E_X = S U + [un-rotation of the quantised product].  The low-rank term joins the product before the
+    // un-rotation, in the rotated domain: (H_left S) (U H_right), added to the scaled accumulators in the GEMM epilogue;
+    // the un-rotation of the sum then returns S U next to the quantised term (the rotations are orthogonal).
+    const float* lr_a = S;
+    if (level >= 2) {
+        ColFwhtArgs c{S, IN_F32, rank, Sp, OUT_F32, rank, Sp, rank, b, rank, ilog2_exact(hb)};
+        if (launch_col_fwht(c, hs) != hipSuccess) return HALO_EHIP;
+        lr_a = Sp;
+    }
+    if (launch_lr_row_fwht(U, m, Up, m, rank, m, level >= 1 ? hm : 0, hs) != hipSuccess) return HALO_EHIP;
+    st = halo_hadamard_quant(E, HALO_BF16, b, n, n, HALO_QUANT_ROWS, 0, level >= 2 ? hb : 0, s_w, Eq, n, s_e, f32,
+                             level >= 2 ? round256((size_t)b * n * 4) : 0, stream);
+    if (st != HALO_OK) return st;
+    const bool left_fused = level >= 2 && left_in_epilogue(b, n, hb);
+    GemmArgs gx{Eq, n, Wq, m, 0, b, m, n, s_e, nullptr, level == 0 ? EX : (void*)c32,
+                (level > 0 || odt == HALO_F32) ? 1 : 0, m, nullptr, 0, HALO_GEMM_AUTO};
+    gx.lr_rank = rank; gx.lr_a = lr_a; gx.lr_b = Up; gx.ld_lrb = m;
+    if (left_fused) { gx.left_stages = 8; gx.config = HALO_GEMM_256x256x64; }
+    if (launch_gemm_i8(gx, hs) != hipSuccess) return HALO_EHIP;
+    if (level == 0) return HALO_OK;
+    if (level >= 2) return from_hip(finish_left_unrotation(c32, b, m, hb, hm, EX, odt, hs, left_fused ? 8 : 0));
+    RowArgs r{};
+    r.in = c32; r.ld_in = m; r.rows = b; r.cols = m; r.out = EX; r.ld_out = m;
+    set_right_block(r, hm);
+    return from_hip(launch_row_transform(r, IN_F32, odt == HALO_BF16 ? OUT_BF16 : OUT_F32, hs));
 }
 
 }  // extern "C"

@@ -169,6 +169,37 @@ def test_linear_desc_errors_and_workspace(lib):
     assert lib.halo_linear_bwd(ctypes.byref(ok), P, P, P, P, P, P, P, None, 0, None) == binding.HALO_EWORKSPACE
 
 
+def test_peft_argument_errors(lib):
+    P = _p(0x1000)
+    ok = binding.make_desc(64, 128, 64, 2)
+    need = binding.halo_peft_workspace_bytes(ok, 16)
+    assert need >= 64 * 128 * 5 + 64 * 64
+    fwd, bwd = lib.halo_peft_fwd, lib.halo_peft_bwd
+    assert fwd(ctypes.byref(ok), 16, P, P, P, P, P, P, P, P, 16, None) == binding.HALO_EWORKSPACE
+    assert fwd(ctypes.byref(ok), 16, P, P, P, P, None, P, P, P, need, None) == binding.HALO_EINVAL
+    assert fwd(ctypes.byref(ok), 0, P, P, P, P, P, P, P, P, need, None) == binding.HALO_EINVAL
+    assert fwd(ctypes.byref(ok), 12, P, P, P, P, P, P, P, P, need, None) == binding.HALO_ESHAPE
+    assert fwd(ctypes.byref(ok), 72, P, P, P, P, P, P, P, P, need, None) == binding.HALO_EUNSUPPORTED
+    assert fwd(ctypes.byref(ok), 16, _p(0x1008), P, P, P, P, P, P, P, need, None) == binding.HALO_EALIGN
+    assert binding.halo_peft_workspace_bytes(ok, 12) == 0
+    # both widths are reduction lengths of a K-step product: multiples of 64
+    narrow = binding.make_desc(64, 96, 64, 0)
+    assert fwd(ctypes.byref(narrow), 16, P, P, P, P, P, P, P, P, 1 << 30, None) == binding.HALO_ESHAPE
+    tensor = binding.make_desc(64, 128, 64, 2, scale_mode=binding.HALO_SCALE_PER_TENSOR)
+    assert fwd(ctypes.byref(tensor), 16, P, P, P, P, P, P, P, P, 1 << 30, None) == binding.HALO_EUNSUPPORTED
+    # backward: something must be wanted, and each output needs its own inputs
+    assert bwd(ctypes.byref(ok), 16, P, P, P, P, P, P, P, None, None, None, P, need, None) == binding.HALO_EINVAL
+    assert bwd(ctypes.byref(ok), 16, None, P, P, P, P, P, P, P, P, P, P, need, None) == binding.HALO_EINVAL
+    assert bwd(ctypes.byref(ok), 16, P, None, P, P, P, P, P, None, P, None, P, need, None) == binding.HALO_EINVAL   # G_U reads X
+    assert bwd(ctypes.byref(ok), 16, P, P, None, P, P, P, P, None, None, P, P, need, None) == binding.HALO_EINVAL   # G_V reads T
+    assert bwd(ctypes.byref(ok), 16, P, P, P, None, P, P, P, P, None, None, P, need, None) == binding.HALO_EINVAL   # E_X reads Wq
+    assert bwd(ctypes.byref(ok), 16, P, P, P, P, P, P, P, P, P, P, P, need - 1, None) == binding.HALO_EWORKSPACE
+    assert bwd(ctypes.byref(ok), 16, P, P, P, P, P, P, P, P, P, P, None, 0, None) == binding.HALO_EWORKSPACE
+    # empty problem: nothing to do, nothing touched
+    empty = binding.make_desc(0, 128, 64, 2)
+    assert fwd(ctypes.byref(empty), 16, P, P, P, P, P, P, P, None, 0, None) == binding.HALO_OK
+
+
 def test_dequant_unrotate_argument_errors(lib):
     f = lib.halo_dequant_unrotate
     A, O = _p(0x1000), _p(0x2000)
