@@ -36,7 +36,7 @@ def parse():
     p.add_argument("--steps", type=int, default=100)
     p.add_argument("--warmup", type=int, default=20)
     p.add_argument("--config", default="c2", help="headline workload: c2 (default) or c3")
-    p.add_argument("--extra-configs", default="c3,c4,c5,c6,c7", help="comma list of further configs reported under `configs`")
+    p.add_argument("--extra-configs", default="c3,c4,c5,c6,c7,c8", help="comma list of further configs reported under `configs`")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--kernel-iters", type=int, default=50, help="launches per kernel for the per-kernel timings")
     p.add_argument("--pmc-target", default="",
@@ -404,6 +404,74 @@ def run_mx6(key, args, dev, copy_gbs, with_oracle):
     return rec
 
 
+def run_peft(key, args, dev, with_oracle, with_parts=True):
+    """Config c8: the HALO-PEFT module, frozen quantised weight + LoRA adapters; a step is its forward pass and its
+    backward pass (E_X and both adapter gradients)."""
+    import numpy as np
+    import torch
+    from paper_2501_02625_amd import binding, inputs
+    cfg = inputs.CONFIGS[key]
+    lin = cfg.linears[0]
+    b, m, n, rank = cfg.tokens, lin.m, lin.n, cfg.peft_rank
+    hm = cfg.had_block_m(m) if cfg.level >= 1 else 0
+    hb = cfg.had_block_b() if cfg.level >= 2 else 0
+    t = inputs.make_linear_inputs(cfg)
+    to_dev = lambda bits: torch.from_numpy(bits.view(np.int16)).to(dev).view(torch.bfloat16)
+    X, W, E, U, V = (to_dev(t[k]) for k in ("X", "W", "E", "U", "V"))
+    Wq, s_w = binding.halo_hadamard_quant(W, had_block=hm)            # once, before fine-tuning: not part of a step
+    del W
+    desc = binding.make_desc(b, m, n, cfg.level, torch.bfloat16, had_block_m=hm, had_block_b=hb)
+    ws = torch.empty((binding.halo_peft_workspace_bytes(desc, rank),), dtype=torch.uint8, device=dev)
+    Y = torch.empty((b, n), dtype=torch.bfloat16, device=dev)
+    T = torch.empty((b, rank), dtype=torch.float32, device=dev)
+    EX = torch.empty((b, m), dtype=torch.bfloat16, device=dev)
+    GU = torch.empty((rank, m), dtype=torch.float32, device=dev)
+    GV = torch.empty((n, rank), dtype=torch.float32, device=dev)
+
+    fwd = lambda: binding.halo_peft_fwd(desc, X, Wq, s_w, U, V, workspace=ws, Y=Y, T=T)
+    bwd = lambda: binding.halo_peft_bwd(desc, E, X, T, Wq, s_w, U, V, workspace=ws, EX=EX, GU=GU, GV=GV)
+
+    def step():
+        fwd()
+        bwd()
+    ms = time_steps(step, args.steps, args.warmup)
+    ops = float(cfg.gemm_ops())
+    it = args.kernel_iters
+    # the same two large products without the adapters (plain layer on the frozen weight, E_X only), for the cost of the
+    # low-rank branch
+    state = binding.LinearState(torch.empty((b, m), dtype=torch.int8, device=dev), torch.empty((b,), dtype=torch.float32, device=dev),
+                                Wq, s_w)
+    lws = torch.empty((max(binding.halo_linear_workspace_bytes(desc), 1),), dtype=torch.uint8, device=dev)
+    parts = None if not with_parts else dict(
+        fwd=time_launches(fwd, it),
+        bwd=time_launches(bwd, it),
+        bwd_ex_only=time_launches(lambda: binding.halo_peft_bwd(desc, E, X, T, Wq, s_w, U, V, workspace=ws, EX=EX,
+                                                                 want_gu=False, want_gv=False), it),
+        bwd_adapter_gradients_only=time_launches(lambda: binding.halo_peft_bwd(desc, E, X, T, Wq, s_w, U, V, workspace=ws,
+                                                                                GU=GU, GV=GV, want_ex=False), it),
+        plain_fwd_frozen_weight=time_launches(lambda: binding.halo_linear_fwd(desc, X, None, state=state, Y=Y), it),
+        plain_bwd_ex_only=time_launches(lambda: binding.halo_linear_bwd(desc, E, state, workspace=lws, EX=EX, want_g=False), it),
+    )
+    rec = dict(workload="%s: HALO-PEFT, tokens %d, frozen INT8 weight %dx%d (n x m), LoRA rank %d, HALO-%d forms of F and E, "
+                        "bf16 in/out, fwd + bwd (E_X, G_U, G_V)" % (key, b, n, m, rank, cfg.level),
+               b=b, m=m, n=n, rank=rank, level=cfg.level, had_block_m=hm, had_block_b=hb, ops_per_step=ops, ms_per_step=ms,
+               value=ops / (ms * 1e-3) / 1e12, unit="TOPS", ms_parts=parts)
+    if with_oracle:
+        from oracle import halo_oracle as orc
+        tokens = 512
+        ts = inputs.make_linear_inputs(cfg, tokens=tokens)
+        Xr, Wr, Er, Ur, Vr = (orc.bf16_bits_to_real(ts[k]) for k in ("X", "W", "E", "U", "V"))
+        base = orc.forward(np.zeros((16, m), np.float32), Wr, cfg.level, hm)
+        c0 = time.perf_counter()
+        orc.peft_forward(Xr, base["Wq"], base["s_w"], Ur, Vr, cfg.level, hm)
+        orc.peft_backward(Er, Xr, base["Wq"], base["s_w"], Ur, Vr, cfg.level, hm, tokens)
+        secs = time.perf_counter() - c0
+        rec["cpu_baseline"] = dict(value=ops * tokens / b / secs / 1e12, unit="TOPS", cores=blas_threads(), kind="oracle",
+                                   seconds=secs, sample="the first %d of %d tokens (all features; left block = %d), "
+                                   "extrapolated by operation count (numpy oracle)" % (tokens, b, tokens))
+    return rec
+
+
 def measure_copy(dev):
     import torch
     src = torch.empty((256 << 20,), dtype=torch.uint8, device=dev)
@@ -463,7 +531,10 @@ def main():
         return
 
     if args.step_only:
-        rec, _, _ = run_single(args.config, args, dev, None, False, False)
+        if inputs.CONFIGS[args.config].peft_rank:
+            rec = run_peft(args.config, args, dev, False, with_parts=False)
+        else:
+            rec, _, _ = run_single(args.config, args, dev, None, False, False)
         print(json.dumps({"metric": METRIC, "value": rec["value"], "unit": "TOPS", "n_gpus": 1, "steps": args.steps,
                           "warmup": args.warmup, "ms_per_step": rec["ms_per_step"], "higher_is_better": True,
                           "step_only": True, "config": {"workload": rec["workload"]}}))
@@ -505,6 +576,8 @@ def main():
         torch.cuda.empty_cache()
         if key == "c5":
             r = run_mx6(key, args, dev, copy_gbs, not args.no_cpu_baseline)
+        elif cfg.peft_rank:
+            r = run_peft(key, args, dev, not args.no_cpu_baseline)
         elif len(cfg.linears) == 1:
             r, Lx, _ = run_single(key, args, dev, copy_gbs, True, not args.no_cpu_baseline)
             del Lx

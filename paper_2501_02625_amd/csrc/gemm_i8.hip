@@ -482,10 +482,9 @@ __device__ __forceinline__ void epilogue_left8(const GemmArgs& a, int64_t m0, in
 // Low-rank side product (a LoRA branch next to the quantised product): turns the int32 accumulators, in place, into the
 // fp32 values
 //   ((float(acc) * row_scale[row]) * col_scale[col]) * post_scale  +  sum_k lr_a[row, k] * lr_b[k, col],
-// the first part rounded exactly as the plain epilogues round it, the sum added by fp32 matrix instructions
-// (v_mfma_f32_32x32x2_f32, whose result layout is that of the int8 instruction: lane l supplies A[row l % 32][k l / 32]
-// and B[k l / 32][col l % 32]) with the scaled accumulator as their addend.  The registers then hold float bit patterns
-// and the PRE variants of the epilogues take over.  Sixteen ranks at a time: their operands are fetched in one batch.
+// the first part rounded exactly as the plain epilogues round it, the sum added by matrix instructions with the scaled
+// accumulator as their addend.  The registers then hold float bit patterns and the PRE variants of the epilogues take
+// over.
 template <class Cfg>
 __device__ __forceinline__ void lowrank_prepare(const GemmArgs& a, int64_t m0, int64_t n0, int wave, int wave_m, int wave_n,
                                                 int lane, v16i (&acc)[Cfg::TM][Cfg::TN], unsigned char* smem) {
@@ -517,34 +516,106 @@ __device__ __forceinline__ void lowrank_prepare(const GemmArgs& a, int64_t m0, i
             for (int j = 0; j < TN; ++j)
                 acc[i][j][r] = __float_as_int((((float)acc[i][j][r] * rs) * cs[j]) * post);
         }
+    // The low-rank sum, sixteen ranks at a time, by bf16 matrix instructions (v_mfma_f32_32x32x16_bf16: lane l supplies
+    // row / column l % 32, ranks 8 (l / 32) .. + 8; the result layout is that of the int8 instruction).  fp32 operands
+    // are split exactly into three bf16 pieces (8 + 8 + 8 mantissa bits, x = hi + mid + lo); every product of two pieces
+    // is exact and is accumulated in fp32.  The products kept are those down to 2^-16 of the full one (all of them when
+    // one operand is bf16 already): what is dropped is below 2^-23 of |a b|, an fp32 rounding.  Smallest terms first.
+    // Every address is clamped into its matrix, so that all loads are unconditional and in flight together; what lies
+    // outside is zeroed afterwards.
+    typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+    typedef uint32_t v4u __attribute__((ext_vector_type(4)));
+    auto hi16 = [](uint32_t x, uint32_t y) { return __builtin_amdgcn_perm(y, x, 0x07060302u); };
+    auto split8 = [&](const float (&x)[8], v8bf& h, v8bf& m, v8bf& l) {
+        uint32_t ph[8], pm[8], pl[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            ph[e] = __float_as_uint(x[e]) & 0xFFFF0000u;
+            const float r1 = x[e] - __uint_as_float(ph[e]);
+            pm[e] = __float_as_uint(r1) & 0xFFFF0000u;
+            pl[e] = __float_as_uint(r1 - __uint_as_float(pm[e]));
+        }
+        h = __builtin_bit_cast(v8bf, (v4u){hi16(ph[0], ph[1]), hi16(ph[2], ph[3]), hi16(ph[4], ph[5]), hi16(ph[6], ph[7])});
+        m = __builtin_bit_cast(v8bf, (v4u){hi16(pm[0], pm[1]), hi16(pm[2], pm[3]), hi16(pm[4], pm[5]), hi16(pm[6], pm[7])});
+        l = __builtin_bit_cast(v8bf, (v4u){hi16(pl[0], pl[1]), hi16(pl[2], pl[3]), hi16(pl[4], pl[5]), hi16(pl[6], pl[7])});
+    };
+    int64_t rowc[TM], colc[TN];
+    bool row_ok[TM], col_ok[TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        const int64_t row = m0 + wave_m * Cfg::WM + i * 32 + lrow;
+        row_ok[i] = row < a.M;
+        rowc[i] = row_ok[i] ? row : a.M - 1;
+    }
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        col_ok[j] = colj[j] < a.N;
+        colc[j] = col_ok[j] ? colj[j] : a.N - 1;
+    }
     for (int c0 = 0; c0 < a.lr_rank; c0 += 16) {
-        float av[TM][8], bv[TN][8];
+        const bool k_ok = c0 + 8 * half < a.lr_rank;            // the rank is a multiple of 8
+        const int kb = k_ok ? c0 + 8 * half : 0;
+        float4 araw[TM][2];
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
-            const int64_t row = m0 + wave_m * Cfg::WM + i * 32 + lrow;
+            const float4* p = reinterpret_cast<const float4*>(a.lr_a + rowc[i] * a.lr_rank + kb);
+            araw[i][0] = p[0];
+            araw[i][1] = p[1];
+        }
+        v8bf bh[TN], bm[TN], bl[TN];
+        if (a.lr_b_bf16) {                 // uniform
+            uint4 braw[TN];
 #pragma unroll
-            for (int kk = 0; kk < 8; ++kk) {
-                const int k = c0 + 2 * kk + half;
-                av[i][kk] = (row < a.M && k < a.lr_rank) ? a.lr_a[row * a.lr_rank + k] : 0.0f;
+            for (int j = 0; j < TN; ++j)
+                braw[j] = *reinterpret_cast<const uint4*>(reinterpret_cast<const uint16_t*>(a.lr_b) + colc[j] * a.lr_rank + kb);
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                if (!(k_ok && col_ok[j])) braw[j] = make_uint4(0u, 0u, 0u, 0u);
+                bh[j] = __builtin_bit_cast(v8bf, braw[j]);
+            }
+        } else {
+            float4 braw[TN][2];
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const float4* p = reinterpret_cast<const float4*>(reinterpret_cast<const float*>(a.lr_b) + colc[j] * a.lr_rank + kb);
+                braw[j][0] = p[0];
+                braw[j][1] = p[1];
+            }
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const bool in = k_ok && col_ok[j];
+                const float x[8] = {in ? braw[j][0].x : 0.0f, in ? braw[j][0].y : 0.0f, in ? braw[j][0].z : 0.0f,
+                                    in ? braw[j][0].w : 0.0f, in ? braw[j][1].x : 0.0f, in ? braw[j][1].y : 0.0f,
+                                    in ? braw[j][1].z : 0.0f, in ? braw[j][1].w : 0.0f};
+                split8(x, bh[j], bm[j], bl[j]);
             }
         }
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int kk = 0; kk < 8; ++kk) {
-                const int k = c0 + 2 * kk + half;
-                bv[j][kk] = (colj[j] < a.N && k < a.lr_rank) ? a.lr_b[(int64_t)k * a.ld_lrb + colj[j]] : 0.0f;
-            }
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
+        for (int i = 0; i < TM; ++i) {
+            const bool in = k_ok && row_ok[i];
+            const float x[8] = {in ? araw[i][0].x : 0.0f, in ? araw[i][0].y : 0.0f, in ? araw[i][0].z : 0.0f,
+                                in ? araw[i][0].w : 0.0f, in ? araw[i][1].x : 0.0f, in ? araw[i][1].y : 0.0f,
+                                in ? araw[i][1].z : 0.0f, in ? araw[i][1].w : 0.0f};
+            v8bf ah, am, al;
+            split8(x, ah, am, al);
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
                 v16f f = __builtin_bit_cast(v16f, acc[i][j]);
-#pragma unroll
-                for (int kk = 0; kk < 8; ++kk)
-                    f = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i][kk], bv[j][kk], f, 0, 0, 0);
+                if (a.lr_b_bf16) {
+                    f = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, bh[j], f, 0, 0, 0);
+                    f = __builtin_amdgcn_mfma_f32_32x32x16_bf16(am, bh[j], f, 0, 0, 0);
+                    f = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, bh[j], f, 0, 0, 0);
+                } else {
+                    f = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, bh[j], f, 0, 0, 0);
+                    f = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, bl[j], f, 0, 0, 0);
+                    f = __builtin_amdgcn_mfma_f32_32x32x16_bf16(am, bm[j], f, 0, 0, 0);
+                    f = __builtin_amdgcn_mfma_f32_32x32x16_bf16(am, bh[j], f, 0, 0, 0);
+                    f = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, bm[j], f, 0, 0, 0);
+                    f = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, bh[j], f, 0, 0, 0);
+                }
                 acc[i][j] = __builtin_bit_cast(v16i, f);
             }
+        }
     }
 }
 
@@ -879,7 +950,7 @@ hipError_t launch_dma(const GemmArgs& a, hipStream_t s, const GemmArgs* a2 = nul
     if (wants_left && !LEFT) return hipErrorInvalidValue;
     auto lr_ok = [](const GemmArgs& g) {
         if (g.lr_rank == 0) return true;
-        return g.lr_rank > 0 && g.lr_rank <= kMaxLowRank && g.lr_a && g.lr_b && g.ld_lrb >= g.N && g.C && !g.acc_out;
+        return g.lr_rank > 0 && g.lr_rank <= kMaxLowRank && g.lr_rank % 8 == 0 && g.lr_a && g.lr_b && g.C && !g.acc_out;
     };
     if (!lr_ok(a) || (a2 && !lr_ok(*a2))) return hipErrorInvalidValue;
     static std::once_flag once;

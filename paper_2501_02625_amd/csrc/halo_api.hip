@@ -138,7 +138,7 @@ hipError_t finish_left_unrotation(float* t, int64_t b, int64_t m, int32_t hb, in
 
 // Scratch of the HALO-PEFT entry points (one layout for both directions).
 struct PeftWorkspace {
-    size_t xq, s_x, vt, eq, s_e, c32, f32, s, sp, up, part, total;
+    size_t xq, s_x, eq, s_e, c32, f32, s, sp, up, part, part_u, total;
 };
 
 PeftWorkspace peft_layout(const halo_linear_desc* d, int32_t rank) {
@@ -147,7 +147,6 @@ PeftWorkspace peft_layout(const halo_linear_desc* d, int32_t rank) {
     const size_t b = (size_t)d->b, m = (size_t)d->m, n = (size_t)d->n, r = (size_t)rank;
     w.xq = off;   off += round256(b * m);
     w.s_x = off;  off += round256(b * 4);
-    w.vt = off;   off += round256(r * n * 4);
     w.eq = off;   off += round256(b * n);
     w.s_e = off;  off += round256(b * 4);
     w.c32 = off;  off += round256(b * m * 4);       // the E product in fp32, before its un-rotation
@@ -157,7 +156,8 @@ PeftWorkspace peft_layout(const halo_linear_desc* d, int32_t rank) {
     w.sp = off;   off += round256(b * r * 4);
     w.up = off;   off += round256(r * m * 4);
     const size_t pn = lr_grad_workspace_floats(d->b, d->n, rank), pm = lr_grad_workspace_floats(d->b, d->m, rank);
-    w.part = off; off += round256((pn > pm ? pn : pm) * 4);
+    w.part = off; off += round256(pn * 4);          // partial sums of G_V
+    w.part_u = off; off += round256(pm * 4);        // partial sums of G_U
     w.total = off;
     return w;
 }
@@ -734,15 +734,13 @@ halo_status halo_peft_fwd(const halo_linear_desc* desc, int32_t rank, const void
     unsigned char* ws = reinterpret_cast<unsigned char*>(workspace);
     int8_t* Xq = reinterpret_cast<int8_t*>(ws + L.xq);
     float* s_x = reinterpret_cast<float*>(ws + L.s_x);
-    float* vt = reinterpret_cast<float*>(ws + L.vt);
     hipStream_t hs = reinterpret_cast<hipStream_t>(stream);
 
     st = halo_hadamard_quant(X, HALO_BF16, b, m, m, HALO_QUANT_ROWS, hm, 0, nullptr, Xq, m, s_x, nullptr, 0, stream);
     if (st != HALO_OK) return st;
     if (launch_lr_down(X, m, U, 0, m, T, b, m, rank, hs) != hipSuccess) return HALO_EHIP;
-    if (launch_lr_transpose(V, vt, n, rank, hs) != hipSuccess) return HALO_EHIP;
     GemmArgs g{Xq, m, Wq, m, 1, b, n, m, s_x, s_w, Y, desc->out_dt == HALO_F32 ? 1 : 0, n, nullptr, 0, HALO_GEMM_AUTO};
-    g.lr_rank = rank; g.lr_a = T; g.lr_b = vt; g.ld_lrb = n;
+    g.lr_rank = rank; g.lr_a = T; g.lr_b = V; g.lr_b_bf16 = 1;      // V as it is, [n x rank]
     return from_hip(launch_gemm_i8(g, hs));
 }
 
@@ -768,7 +766,6 @@ halo_status halo_peft_bwd(const halo_linear_desc* desc, int32_t rank, const void
     const halo_dtype odt = (halo_dtype)desc->out_dt;
     const int level = desc->level;
     unsigned char* ws = reinterpret_cast<unsigned char*>(workspace);
-    float* vt = reinterpret_cast<float*>(ws + L.vt);
     int8_t* Eq = reinterpret_cast<int8_t*>(ws + L.eq);
     float* s_e = reinterpret_cast<float*>(ws + L.s_e);
     float* c32 = reinterpret_cast<float*>(ws + L.c32);
@@ -777,34 +774,37 @@ halo_status halo_peft_bwd(const halo_linear_desc* desc, int32_t rank, const void
     float* Sp = reinterpret_cast<float*>(ws + L.sp);
     float* Up = reinterpret_cast<float*>(ws + L.up);
     float* part = reinterpret_cast<float*>(ws + L.part);
+    float* part_u = reinterpret_cast<float*>(ws + L.part_u);
     hipStream_t hs = reinterpret_cast<hipStream_t>(stream);
 
     // ---- the thin products: S = E V, G_V = E^T T, G_U = S^T X
-    if (EX || GU) {
-        if (launch_lr_transpose(V, vt, n, rank, hs) != hipSuccess) return HALO_EHIP;
-        if (launch_lr_down(E, n, vt, 1, n, S, b, n, rank, hs) != hipSuccess) return HALO_EHIP;
+    if ((EX || GU) && launch_lr_down(E, n, V, 1, rank, S, b, n, rank, hs) != hipSuccess) return HALO_EHIP;
+    {
+        const LrGradArgs gv{E, n, T, GV, 0, part, n}, gu{X, m, S, GU, 1, part_u, m};
+        if (launch_lr_grads(GV ? &gv : nullptr, GU ? &gu : nullptr, b, rank, hs) != hipSuccess) return HALO_EHIP;
     }
-    if (GV && launch_lr_grad(E, n, T, GV, 0, part, b, n, rank, hs) != hipSuccess) return HALO_EHIP;
-    if (GU && launch_lr_grad(X, m, S, GU, 1, part, b, m, rank, hs) != hipSuccess) return HALO_EHIP;
     if (!EX) return HALO_OK;
 
     // ---- E_X = S U + [un-rotation of the quantised product].  The low-rank term joins the product before the
     // un-rotation, in the rotated domain: (H_left S) (U H_right), added to the scaled accumulators in the GEMM epilogue;
     // the un-rotation of the sum then returns S U next to the quantised term (the rotations are orthogonal).
     const float* lr_a = S;
-    if (level >= 2) {
+    const bool rotate_s = level >= 2;
+    const bool s_small = rotate_s && lr_col_fwht_shape_ok(b, hb);
+    if (rotate_s) lr_a = Sp;
+    if (launch_lr_rotations(U, Up, rank, m, level >= 1 ? hm : 0, s_small ? S : nullptr, Sp, b, hb, hs) != hipSuccess)
+        return HALO_EHIP;
+    if (rotate_s && !s_small) {            // left blocks too long for one workgroup's LDS: the strided passes
         ColFwhtArgs c{S, IN_F32, rank, Sp, OUT_F32, rank, Sp, rank, b, rank, ilog2_exact(hb)};
         if (launch_col_fwht(c, hs) != hipSuccess) return HALO_EHIP;
-        lr_a = Sp;
     }
-    if (launch_lr_row_fwht(U, m, Up, m, rank, m, level >= 1 ? hm : 0, hs) != hipSuccess) return HALO_EHIP;
     st = halo_hadamard_quant(E, HALO_BF16, b, n, n, HALO_QUANT_ROWS, 0, level >= 2 ? hb : 0, s_w, Eq, n, s_e, f32,
                              level >= 2 ? round256((size_t)b * n * 4) : 0, stream);
     if (st != HALO_OK) return st;
     const bool left_fused = level >= 2 && left_in_epilogue(b, n, hb);
     GemmArgs gx{Eq, n, Wq, m, 0, b, m, n, s_e, nullptr, level == 0 ? EX : (void*)c32,
                 (level > 0 || odt == HALO_F32) ? 1 : 0, m, nullptr, 0, HALO_GEMM_AUTO};
-    gx.lr_rank = rank; gx.lr_a = lr_a; gx.lr_b = Up; gx.ld_lrb = m;
+    gx.lr_rank = rank; gx.lr_a = lr_a; gx.lr_b = Up;                 // (U H)^T, [m x rank]
     if (left_fused) { gx.left_stages = 8; gx.config = HALO_GEMM_256x256x64; }
     if (launch_gemm_i8(gx, hs) != hipSuccess) return HALO_EHIP;
     if (level == 0) return HALO_OK;

@@ -146,11 +146,12 @@ struct GemmArgs {
     // lr_rank > 0 (C required, no acc_out; K-step configurations only): the epilogue adds a low-rank product to the
     // scaled accumulators before anything else happens to them,
     //   value(row, col) = ((float(acc) * row_scale[row]) * col_scale[col]) * post_scale + sum_k lr_a[row, k] * lr_b[k, col]
-    // with lr_a fp32 [M x lr_rank] (dense rows) and lr_b fp32 [lr_rank x N] (row pitch ld_lrb), fp32 matrix instructions.
+    // with lr_a fp32 [M x lr_rank] and lr_b [N x lr_rank] (fp32, or bf16 with lr_b_bf16), both dense, 16-byte aligned,
+    // lr_rank a multiple of 8; the sum is accumulated in fp32.
     int lr_rank;
     const float* lr_a;
-    const float* lr_b;
-    int64_t ld_lrb;
+    const void* lr_b;
+    int lr_b_bf16;
 };
 constexpr int kMaxLowRank = 64;
 hipError_t launch_gemm_i8(const GemmArgs& a, hipStream_t s);
@@ -161,20 +162,31 @@ bool gemm_config_valid(int cfg, int64_t K);
 hipError_t launch_mfma_i8_probe(const int8_t* operands, int iters, int32_t* sink, hipStream_t s);
 
 // ---- low-rank side branch (LoRA adapters next to the quantised products) ----
-// out fp32 [rows x rank] = in bf16 [rows x K] * bt[rank x K]^T; bt bf16, or fp32 holding bf16-representable values.
-hipError_t launch_lr_down(const void* in, int64_t ld_in, const void* bt, int bt_is_f32, int64_t ld_b, float* out,
-                          int64_t rows, int64_t K, int rank, hipStream_t s);
+// out fp32 [rows x rank] = in bf16 [rows x K] times the thin bf16 operand: [rank x K] (its transpose is applied), or
+// [K x rank] with k_major.  K a multiple of 64.
+hipError_t launch_lr_down(const void* in, int64_t ld_in, const void* thin, int k_major, int64_t ld_b, float* out, int64_t rows,
+                          int64_t K, int rank, hipStream_t s);
 // out = big^T small: big bf16 [rows x wide], small fp32 [rows x rank] dense; out fp32 [wide x rank], or its transpose
-// [rank x wide] with transpose_out.  part: lr_grad_workspace_floats(rows, wide, rank) floats of scratch.
+// [rank x wide] with transpose_out.  part: lr_grad_workspace_floats(rows, wide, rank) floats of scratch.  Two such
+// products over the same rows ride in one launch (either pointer may be null).
+struct LrGradArgs {
+    const void* big;
+    int64_t ld_big;
+    const float* small;
+    float* out;
+    int transpose_out;
+    float* part;
+    int64_t wide;
+};
 size_t lr_grad_workspace_floats(int64_t rows, int64_t wide, int rank);
-hipError_t launch_lr_grad(const void* big, int64_t ld_big, const float* small, float* out, int transpose_out, float* part,
-                          int64_t rows, int64_t wide, int rank, hipStream_t s);
-// out fp32 [rank x n] = transpose of in bf16 [n x rank].
-hipError_t launch_lr_transpose(const void* in, float* out, int64_t n, int rank, hipStream_t s);
-// out fp32 = in bf16 [rows x cols] with every row rotated in blocks of `block` (2^n, or 28 * 2^n; 0: only widened).
+hipError_t launch_lr_grads(const LrGradArgs* a, const LrGradArgs* b, int64_t rows, int rank, hipStream_t s);
+// The rotated forms of the thin operands of the E_X epilogue, one launch:  u_rot fp32 [m x rank] = the TRANSPOSE of u bf16
+// [rank x m] with every row rotated in blocks of block_m (2^n, or 28 * 2^n; <= 1: only widened), and sm_rot fp32
+// [b x rank] = sm fp32 [b x rank] with every column rotated in blocks of block_b (a power of two).  Either pair may be null.
 bool lr_row_fwht_shape_ok(int64_t cols, int64_t block);
-hipError_t launch_lr_row_fwht(const void* in, int64_t ld_in, float* out, int64_t ld_out, int64_t rows, int64_t cols,
-                              int64_t block, hipStream_t s);
+bool lr_col_fwht_shape_ok(int64_t rows, int64_t block);
+hipError_t launch_lr_rotations(const void* u, float* u_rot, int64_t rank, int64_t m, int64_t block_m, const float* sm,
+                               float* sm_rot, int64_t b, int64_t block_b, hipStream_t s);
 
 // ---- MXFP6 GEMM: C[M x N] = A[M x K] B[N x K]^T on packed E3M2 codes with one E8M0 scale per 32 elements along K ----
 struct Mx6GemmArgs {

@@ -2,7 +2,7 @@
 // "Parameter Efficient Fine Tuning"; Appendix "LoRA-style Linear Module and HALO for PEFT"):
 //   T = X U^T,  S = E_Y V            (tall input times a thin matrix: lr_down_kernel, bf16 matrix instructions)
 //   G_V = E_Y^T T,  G_U = S^T X      (thin result, reduction over the tokens: lr_grad_kernel + lr_reduce_kernel)
-// and the small helpers that bring V and U into the form the GEMM epilogue wants (fp32, rank-major).  The additions
+// and the small helpers that bring V and U into the form the GEMM epilogue wants (rank-major; U rotated).  The additions
 // T V^T and S U themselves happen in the epilogue of the INT8 GEMM.  All inputs are bf16, every product accumulates in
 // fp32 and the intermediates T and S stay fp32.  Every kernel here is bound by one read of its tall operand from HBM.
 #pragma clang fp contract(off)
@@ -15,65 +15,104 @@ namespace {
 typedef float v4f __attribute__((ext_vector_type(4)));
 typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 
+typedef uint32_t v4u __attribute__((ext_vector_type(4)));
+
 __device__ __forceinline__ float bf16_to_f32(uint32_t bits16) { return __uint_as_float(bits16 << 16); }
 
-// ------------------------------------------------------------------------------------------------ down-projection
-// out[row, c] = sum_k in[row, k] * bt[c, k]:  in bf16 [rows x K] (pitch ld_in), bt [rank x K] (pitch ld_b) either bf16 or
-// fp32 holding bf16-representable values, out fp32 [rows x rank] dense.  K a multiple of 32, rank <= 64.
-// A workgroup owns 16 rows; its eight wavefronts take the 32-element K chunks round robin (v_mfma_f32_16x16x32_bf16:
-// lane l supplies row l % 16, elements 8 (l / 16) .. + 8 of the chunk, for both operands; result lane l holds column
-// l % 16, rows 4 (l / 16) .. + 4) and their partial sums meet in LDS, added in wavefront order.
-constexpr int kDownWaves = 8;
+// (high half of y) << 16 | (high half of x), and the same for the low halves: two bf16 values side by side.
+__device__ __forceinline__ uint32_t pack_hi(uint32_t x, uint32_t y) { return __builtin_amdgcn_perm(y, x, 0x07060302u); }
+__device__ __forceinline__ uint32_t pack_lo(uint32_t x, uint32_t y) { return __builtin_amdgcn_perm(y, x, 0x05040100u); }
 
-template <bool B_F32>
+// x = hi + mid + lo exactly, each piece an fp32 value whose low 16 bits are zero (a bf16): truncating the 24-bit mantissa
+// to its top 8 bits, subtracting (exact), and again; what is left has at most 8 significant bits.
+__device__ __forceinline__ void split3(float x, uint32_t& hi, uint32_t& mid, uint32_t& lo) {
+    hi = __float_as_uint(x) & 0xFFFF0000u;
+    const float r1 = x - __uint_as_float(hi);
+    mid = __float_as_uint(r1) & 0xFFFF0000u;
+    lo = __float_as_uint(r1 - __uint_as_float(mid));
+}
+
+// ------------------------------------------------------------------------------------------------ down-projection
+// out[row, c] = sum_k in[row, k] * B[k, c]:  in bf16 [rows x K] (pitch ld_in), out fp32 [rows x rank] dense.  The thin
+// operand is bf16 in either orientation: [rank x K] (K-contiguous rows, pitch ld_b: the adapter U for T = X U^T) or,
+// with KMAJOR, [K x rank] (pitch ld_b: the adapter V for S = E V).  K a multiple of 64, rank <= 64 (NTILE rank tiles of 16).
+// A workgroup owns 16 rows; its sixteen wavefronts take pairs of 32-element K chunks round robin (a pair is one
+// 128-byte line of every row).  v_mfma_f32_16x16x32_bf16: lane l supplies row l % 16, elements 8 (l / 16) .. + 8 of the
+// chunk, for both operands; result lane l holds column l % 16, rows 4 (l / 16) .. + 4.  The partial sums meet in LDS and
+// are added in wavefront order.
+constexpr int kDownWaves = 16;
+
+template <bool KMAJOR>
+__device__ __forceinline__ v8bf lr_load_b(const uint16_t* __restrict__ bt, int64_t ld_b, int c, int64_t k) {
+    if constexpr (KMAJOR) {
+        // eight rows of the [K x rank] matrix, one element each
+        uint32_t e[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) e[u] = bt[(k + u) * ld_b + c];
+        const v4u packed = {pack_lo(e[0], e[1]), pack_lo(e[2], e[3]), pack_lo(e[4], e[5]), pack_lo(e[6], e[7])};
+        return __builtin_bit_cast(v8bf, packed);
+    } else {
+        return *reinterpret_cast<const v8bf*>(bt + (int64_t)c * ld_b + k);
+    }
+}
+
+template <int NTILE, bool KMAJOR>
 __global__ void __launch_bounds__(64 * kDownWaves)
-lr_down_kernel(const uint16_t* __restrict__ in, int64_t ld_in, const void* __restrict__ bt, int64_t ld_b,
+lr_down_kernel(const uint16_t* __restrict__ in, int64_t ld_in, const uint16_t* __restrict__ bt, int64_t ld_b,
                float* __restrict__ out, int64_t rows, int64_t K, int rank) {
-    __shared__ float s_part[kDownWaves][4][4][64];      // [wavefront][rank tile][register][lane]
+    __shared__ float s_part[kDownWaves][NTILE][4][64];      // [wavefront][rank tile][register][lane]
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int lr = lane & 15, kg = lane >> 4;
     const int64_t row0 = (int64_t)blockIdx.x * 16;
     int64_t row = row0 + lr;
     if (row > rows - 1) row = rows - 1;                 // clamped rows are computed and never stored
     const uint16_t* ap = in + row * ld_in + kg * 8;
-    const int ntile = (rank + 15) >> 4;
-    v4f acc[4];
+    // columns beyond the rank are replaced by column 0; their results are never stored
+    int cb[NTILE];
 #pragma unroll
-    for (int t = 0; t < 4; ++t) acc[t] = v4f{0.0f, 0.0f, 0.0f, 0.0f};
+    for (int t = 0; t < NTILE; ++t) cb[t] = (t * 16 + lr) < rank ? (t * 16 + lr) : 0;
+    v4f acc[NTILE];
+#pragma unroll
+    for (int t = 0; t < NTILE; ++t) acc[t] = v4f{0.0f, 0.0f, 0.0f, 0.0f};
 
-
-    for (int64_t k0 = (int64_t)wave * 32; k0 < K; k0 += kDownWaves * 32) {
-        const v8bf a = *reinterpret_cast<const v8bf*>(ap + k0);
+    constexpr int64_t STEP = kDownWaves * 64;
+    constexpr int UNR = NTILE <= 2 ? 4 : 2;              // chunk pairs per trip, all loads issued before the first product
+    int64_t k0 = (int64_t)wave * 64;
+    for (; k0 + (UNR - 1) * STEP < K; k0 += UNR * STEP) {
+        v8bf a[UNR][2], b[UNR][2][NTILE];
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            if (t >= ntile) break;                      // uniform
-            const int c = t * 16 + lr;
-            v8bf b;
-            if (c < rank) {
-                if constexpr (B_F32) {
-                    const float* bp = reinterpret_cast<const float*>(bt) + (int64_t)c * ld_b + k0 + kg * 8;
-                    const float4 lo = *reinterpret_cast<const float4*>(bp);
-                    const float4 hi = *reinterpret_cast<const float4*>(bp + 4);
-                    // the values are bf16-representable: the conversion is exact
-                    b = v8bf{(__bf16)lo.x, (__bf16)lo.y, (__bf16)lo.z, (__bf16)lo.w,
-                             (__bf16)hi.x, (__bf16)hi.y, (__bf16)hi.z, (__bf16)hi.w};
-                } else {
-                    b = *reinterpret_cast<const v8bf*>(reinterpret_cast<const uint16_t*>(bt) + (int64_t)c * ld_b + k0 + kg * 8);
-                }
-            } else {
+        for (int u = 0; u < UNR; ++u)
 #pragma unroll
-                for (int e = 0; e < 8; ++e) b[e] = (__bf16)0.0f;
+            for (int h = 0; h < 2; ++h) {
+                const int64_t k = k0 + u * STEP + h * 32;
+                a[u][h] = *reinterpret_cast<const v8bf*>(ap + k);
+#pragma unroll
+                for (int t = 0; t < NTILE; ++t) b[u][h][t] = lr_load_b<KMAJOR>(bt, ld_b, cb[t], k + kg * 8);
             }
-            acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, acc[t], 0, 0, 0);
+#pragma unroll
+        for (int u = 0; u < UNR; ++u)
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+#pragma unroll
+                for (int t = 0; t < NTILE; ++t)
+                    acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[u][h], b[u][h][t], acc[t], 0, 0, 0);
+    }
+    for (; k0 < K; k0 += STEP) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int64_t k = k0 + h * 32;
+            const v8bf a = *reinterpret_cast<const v8bf*>(ap + k);
+#pragma unroll
+            for (int t = 0; t < NTILE; ++t)
+                acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, lr_load_b<KMAJOR>(bt, ld_b, cb[t], k + kg * 8), acc[t], 0, 0, 0);
         }
     }
 #pragma unroll
-    for (int t = 0; t < 4; ++t)
+    for (int t = 0; t < NTILE; ++t)
 #pragma unroll
         for (int v = 0; v < 4; ++v) s_part[wave][t][v][lane] = acc[t][v];
     __syncthreads();
-    // 4 tiles x 4 registers x 64 lanes = 1024 sums, two per thread
-    for (int idx = threadIdx.x; idx < ntile * 256; idx += 64 * kDownWaves) {
+    for (int idx = threadIdx.x; idx < NTILE * 256; idx += 64 * kDownWaves) {
         const int t = idx >> 8, v = (idx >> 6) & 3, l = idx & 63;
         float sum = s_part[0][t][v][l];
 #pragma unroll
@@ -85,27 +124,47 @@ lr_down_kernel(const uint16_t* __restrict__ in, int64_t ld_in, const void* __res
 }
 
 // ------------------------------------------------------------------------------------------------ adapter gradients
-// part[split][col][c] = sum over the tokens t of the split of big[t, col] * small[t, c]:  big bf16 [rows x wide] (pitch
+// part[split] = sum over the tokens t of the split of big[t, col] * small[t, c]:  big bf16 [rows x wide] (pitch
 // ld_big), small fp32 [rows x rank] dense.  A workgroup owns 128 columns of `big` and one range of tokens; its four
-// wavefronts take groups of four tokens round robin.  v_mfma_f32_16x16x4_f32 (lane l supplies A[i = l % 16][k = l / 16]
-// and B[k = l / 16][j = l % 16]; result lane l holds j = l % 16, i = 4 (l / 16) .. + 4) with k = token, j = rank index
-// and i = one of sixteen columns: a lane loads 8 consecutive columns of one token (16 bytes), and the v-th of them feeds
-// the v-th of eight instructions, so instruction v covers columns c0 + 8 i + v.  NTILE = rank tiles of 16.
+// wavefronts take groups of 32 tokens round robin.  v_mfma_f32_16x16x32_bf16 with k = token: lane l supplies, for row
+// (A) / column (B) l % 16, the eight tokens 8 (l / 16) .. + 8 of the group.  `big` is read row-wise, 8 consecutive columns
+// of one token per load (16 bytes), one load for each of the lane's eight tokens; the v-th column of the eight loads,
+// packed with byte permutes, is the A operand of the v-th instruction, which therefore covers columns c0 + 8 i + v.
+// `small` is fp32: every value is split exactly into three bf16 pieces (8 + 8 + 8 mantissa bits; x = hi + mid + lo), each
+// piece multiplied by the bf16 `big` exactly and accumulated in fp32, so the result is that of an fp32 product sum.
+// NTILE = rank tiles of 16.  The partial result is laid out like the final one: [wide x rank], or [rank x wide] with
+// `transpose`.  Two independent products ride in one launch (blockIdx.z): G_V = E^T T and G_U = S^T X.
 constexpr int kGradWaves = 4;
+
+struct GradJob {
+    const uint16_t* big;
+    int64_t ld_big;
+    const float* small;
+    float* part;             // [splits][wide * rank], or the result itself when splits == 1
+    int64_t rows, wide;
+    int64_t rows_per_split;
+    int splits;
+    int transpose;
+};
 
 template <int NTILE>
 __global__ void __launch_bounds__(64 * kGradWaves)
-lr_grad_kernel(const uint16_t* __restrict__ big, int64_t ld_big, const float* __restrict__ small, float* __restrict__ part,
-               int64_t rows, int64_t wide, int rank, int64_t rows_per_split) {
-    __shared__ float s_sum[NTILE * 8 * 4][64];
+lr_grad_kernel(GradJob j0, GradJob j1, int rank) {
+    __shared__ float s_sum[kGradWaves][32][64];          // one rank tile of every wavefront: [v * 4 + e][lane]
+    const GradJob& g = blockIdx.z == 0 ? j0 : j1;
+    const int64_t wide = g.wide;
+    const int64_t c0 = (int64_t)blockIdx.x * 128;
+    if (c0 >= wide || (int)blockIdx.y >= g.splits) return;           // uniform over the workgroup
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int i16 = lane & 15, kq = lane >> 4;
-    const int64_t c0 = (int64_t)blockIdx.x * 128;
     const int64_t col = c0 + 8 * i16;
     const bool col_ok = col < wide;                      // wide is a multiple of 8
-    const int64_t t_begin = (int64_t)blockIdx.y * rows_per_split;
-    int64_t t_end = t_begin + rows_per_split;
-    if (t_end > rows) t_end = rows;
+    const int64_t t_begin = (int64_t)blockIdx.y * g.rows_per_split;
+    int64_t t_end = t_begin + g.rows_per_split;
+    if (t_end > g.rows) t_end = g.rows;
+    const uint16_t* __restrict__ big = g.big;
+    const float* __restrict__ small = g.small;
+    const int64_t ld_big = g.ld_big;
 
     v4f acc[NTILE][8];
 #pragma unroll
@@ -113,86 +172,121 @@ lr_grad_kernel(const uint16_t* __restrict__ big, int64_t ld_big, const float* __
 #pragma unroll
         for (int v = 0; v < 8; ++v) acc[t][v] = v4f{0.0f, 0.0f, 0.0f, 0.0f};
 
-
-    for (int64_t t0 = t_begin + wave * 4; t0 < t_end; t0 += kGradWaves * 4) {
-        const int64_t tr = t0 + kq;
-        const bool ok = tr < t_end;
-        uint4 raw = make_uint4(0u, 0u, 0u, 0u);
-        if (ok && col_ok) raw = *reinterpret_cast<const uint4*>(big + tr * ld_big + col);
-        float sv[NTILE];
+    // rows beyond the range and columns beyond the matrix: the address is clamped, the loaded value zeroed
+    const int64_t colc = col_ok ? col : 0;
+    constexpr int64_t STEP = kGradWaves * 32;
+    for (int64_t t0 = t_begin + wave * 32; t0 < t_end; t0 += STEP) {
+        uint4 raw[8];
+        float sv[NTILE][8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int64_t tr = t0 + 8 * kq + u;
+            const bool ok = tr < t_end;
+            const int64_t trc = ok ? tr : t_end - 1;
+            raw[u] = *reinterpret_cast<const uint4*>(big + trc * ld_big + colc);
+            if (!(ok && col_ok)) raw[u] = make_uint4(0u, 0u, 0u, 0u);
+#pragma unroll
+            for (int t = 0; t < NTILE; ++t) {
+                const int c = t * 16 + i16;
+                const float x = small[trc * rank + (c < rank ? c : 0)];
+                sv[t][u] = (ok && c < rank) ? x : 0.0f;
+            }
+        }
+        // B operands: the three bf16 pieces of the eight tokens' values, packed two to a register
+        v8bf bp[NTILE][3];
 #pragma unroll
         for (int t = 0; t < NTILE; ++t) {
-            const int c = t * 16 + i16;
-            sv[t] = (ok && c < rank) ? small[tr * rank + c] : 0.0f;
+            uint32_t piece[3][8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) split3(sv[t][u], piece[0][u], piece[1][u], piece[2][u]);
+#pragma unroll
+            for (int q = 0; q < 3; ++q) {
+                const v4u packed = {pack_hi(piece[q][0], piece[q][1]), pack_hi(piece[q][2], piece[q][3]),
+                                    pack_hi(piece[q][4], piece[q][5]), pack_hi(piece[q][6], piece[q][7])};
+                bp[t][q] = __builtin_bit_cast(v8bf, packed);
+            }
         }
-        const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
 #pragma unroll
         for (int v = 0; v < 8; ++v) {
-            const float a = (v & 1) ? __uint_as_float(w[v >> 1] & 0xFFFF0000u) : __uint_as_float(w[v >> 1] << 16);
+            // column v of the eight tokens: the low or the high half of dword v / 2 of every load
+            uint32_t w[8];
 #pragma unroll
-            for (int t = 0; t < NTILE; ++t) acc[t][v] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, sv[t], acc[t][v], 0, 0, 0);
-        }
-    }
-    // the four wavefronts add their sums in LDS one after the other (a fixed order)
-    for (int w = 0; w < kGradWaves; ++w) {
-        if (wave == w) {
+            for (int u = 0; u < 8; ++u) w[u] = (v >> 1) == 0 ? raw[u].x : (v >> 1) == 1 ? raw[u].y : (v >> 1) == 2 ? raw[u].z : raw[u].w;
+            v4u packed;
+            if (v & 1) packed = v4u{pack_hi(w[0], w[1]), pack_hi(w[2], w[3]), pack_hi(w[4], w[5]), pack_hi(w[6], w[7])};
+            else packed = v4u{pack_lo(w[0], w[1]), pack_lo(w[2], w[3]), pack_lo(w[4], w[5]), pack_lo(w[6], w[7])};
+            const v8bf a = __builtin_bit_cast(v8bf, packed);
 #pragma unroll
             for (int t = 0; t < NTILE; ++t)
 #pragma unroll
-                for (int v = 0; v < 8; ++v)
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        float* p = &s_sum[(t * 8 + v) * 4 + e][lane];
-                        *p = (w == 0) ? acc[t][v][e] : *p + acc[t][v][e];
-                    }
+                for (int q = 0; q < 3; ++q) acc[t][v] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bp[t][q], acc[t][v], 0, 0, 0);
         }
-        __syncthreads();
     }
-    if (wave == 0) {
+    // The wavefronts' sums meet in LDS, one rank tile at a time, and are added in wavefront order; wavefront w then
+    // stores the columns v = 2 w, 2 w + 1 of every group of eight.
+    float* dst = g.part + (int64_t)blockIdx.y * wide * rank;
 #pragma unroll
-        for (int t = 0; t < NTILE; ++t)
+    for (int t = 0; t < NTILE; ++t) {
+        if (t > 0) __syncthreads();
 #pragma unroll
-            for (int v = 0; v < 8; ++v)
+        for (int v = 0; v < 8; ++v)
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const int64_t oc = c0 + 8 * (4 * kq + e) + v;
-                    const int c = t * 16 + i16;
-                    if (oc < wide && c < rank)
-                        part[((int64_t)blockIdx.y * wide + oc) * rank + c] = s_sum[(t * 8 + v) * 4 + e][lane];
-                }
+            for (int e = 0; e < 4; ++e) s_sum[wave][v * 4 + e][lane] = acc[t][v][e];
+        __syncthreads();
+        const int c = t * 16 + i16;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            float o[2];
+#pragma unroll
+            for (int d = 0; d < 2; ++d) {
+                const int q = (2 * wave + d) * 4 + e;
+                float sum = s_sum[0][q][lane];
+#pragma unroll
+                for (int w = 1; w < kGradWaves; ++w) sum += s_sum[w][q][lane];
+                o[d] = sum;
+            }
+            const int64_t oc = c0 + 8 * (4 * kq + e) + 2 * wave;     // columns oc, oc + 1
+            if (oc >= wide || c >= rank) continue;
+            if (g.transpose) {
+                *reinterpret_cast<float2*>(dst + (int64_t)c * wide + oc) = make_float2(o[0], o[1]);
+            } else {
+                dst[oc * rank + c] = o[0];
+                dst[(oc + 1) * rank + c] = o[1];
+            }
+        }
     }
 }
 
-// out = sum over the splits, in order.  transpose_out: out[c * wide + col] (a [rank x wide] result), else
-// out[col * rank + c].
+// out[i] = sum over the splits of part[s][i], in order; four consecutive elements per thread (total a multiple of 4).
+// All partial sums are fetched before the first addition (absent ones count as zero).  blockIdx.y picks the job.
+struct ReduceJob {
+    const float* part;
+    float* out;
+    int64_t total;
+    int splits;
+};
+constexpr int kMaxGradSplits = 16;
+
 __global__ void __launch_bounds__(256)
-lr_reduce_kernel(const float* __restrict__ part, float* __restrict__ out, int64_t wide, int rank, int splits,
-                 int transpose_out) {
-    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    const int64_t total = wide * rank;
-    if (idx >= total) return;
-    float sum = part[idx];
-    for (int s = 1; s < splits; ++s) sum += part[(int64_t)s * total + idx];
-    if (transpose_out) {
-        const int64_t colw = idx / rank;
-        const int c = (int)(idx % rank);
-        out[(int64_t)c * wide + colw] = sum;
-    } else {
-        out[idx] = sum;
+lr_reduce_kernel(ReduceJob r0, ReduceJob r1) {
+    const ReduceJob& r = blockIdx.y == 0 ? r0 : r1;
+    const int64_t idx = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
+    if (idx >= r.total || r.splits <= 1) return;
+    float4 p[kMaxGradSplits];
+#pragma unroll
+    for (int s = 0; s < kMaxGradSplits; ++s) {
+        const int sc = s < r.splits ? s : 0;
+        p[s] = *reinterpret_cast<const float4*>(r.part + (int64_t)sc * r.total + idx);
     }
+    float4 sum = p[0];
+#pragma unroll
+    for (int s = 1; s < kMaxGradSplits; ++s) {
+        if (s < r.splits) { sum.x += p[s].x; sum.y += p[s].y; sum.z += p[s].z; sum.w += p[s].w; }
+    }
+    *reinterpret_cast<float4*>(r.out + idx) = sum;
 }
 
 // ------------------------------------------------------------------------------------------------ small helpers
-// out[k * n + j] = float(in[j * rank + k]):  V bf16 [n x rank]  ->  V^T fp32 [rank x n].
-__global__ void __launch_bounds__(256)
-lr_transpose_kernel(const uint16_t* __restrict__ in, float* __restrict__ out, int64_t n, int rank) {
-    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (idx >= n * rank) return;
-    const int64_t j = idx / rank;
-    const int k = (int)(idx % rank);
-    out[(int64_t)k * n + j] = bf16_to_f32(in[idx]);
-}
-
 // Sign rows of the order-28 Hadamard matrix (bit c of row r set: entry +1), built like the row kernel's: Paley's second
 // construction from the quadratic character modulo 13.  The matrix is symmetric.
 constexpr int lr_chi13(int a) {
@@ -220,24 +314,47 @@ constexpr H28Rows make_h28_rows() {
 }
 __device__ const H28Rows kH28Rows = make_h28_rows();
 
-// out[row, :] = in[row, :] rotated in blocks of `block` elements (block = 2^n, or 28 * 2^n: H_{2^n} (x) H_28 with element
-// i * 28 + j indexed by i in the Walsh-Hadamard factor), normalised; block <= 1: a plain conversion.  bf16 in, fp32 out,
-// a handful of rows (the adapter U): one workgroup per (row, block), the block in LDS.  The order of the additions is
-// not that of the row kernels; nothing here needs to be reproducible to the bit against a reference.
-constexpr int kSmallFwhtMax = 14336;
+// Rotations of thin matrices, each vector in LDS: a job is a set of vectors of `block` elements (block = 2^n, or
+// 28 * 2^n: H_{2^n} (x) H_28 with element i * 28 + j indexed by i in the Walsh-Hadamard factor; block 64 with
+// log_p = -1: no rotation, only the conversion), element e of vector (a, b) at  a * stride_a + b * stride_b + e * stride_e
+// in the source and at the same expression with the dst_ strides in the destination.  bf16 or fp32 in, fp32 out, normalised.  One workgroup per vector; the first
+// job's vectors come first in the grid.  The order of the additions is not that of the row kernels; nothing here needs to
+// be reproducible to the bit against a reference.  Used for U H (rows of the adapter U) and H S (columns of S = E V).
+constexpr int kSmallFwhtMax = 16384;
+constexpr int kSmallFwhtThreads = 1024;
 
-__global__ void __launch_bounds__(256)
-lr_row_fwht_kernel(const uint16_t* __restrict__ in, int64_t ld_in, float* __restrict__ out, int64_t ld_out, int block,
-                   int unit, float c_norm) {
+struct FwhtJob {
+    const void* src;
+    float* dst;
+    int src_bf16;
+    int64_t stride_a, stride_b, stride_e;
+    int64_t dst_a, dst_b, dst_e;     // the same three strides in the destination
+    int count_b;             // vectors per a
+    int vectors;             // count_a * count_b
+    int block, unit, log_p;  // unit 1 or 28; log_p = log2(block / unit), or -1
+    float c_norm;
+};
+
+__global__ void __launch_bounds__(kSmallFwhtThreads)
+lr_small_fwht_kernel(FwhtJob j0, FwhtJob j1) {
     __shared__ float s_x[kSmallFwhtMax];
-    const int64_t row = blockIdx.y;
-    const int64_t base = (int64_t)blockIdx.x * block;
-    const uint16_t* src = in + row * ld_in + base;
-    for (int i = threadIdx.x; i < block; i += 256) s_x[i] = bf16_to_f32(src[i]);
+    const bool first = (int)blockIdx.x < j0.vectors;
+    const FwhtJob& g = first ? j0 : j1;
+    const int vec = first ? (int)blockIdx.x : (int)blockIdx.x - j0.vectors;
+    const int64_t va = vec / g.count_b, vb = vec % g.count_b;
+    const int64_t base = va * g.stride_a + vb * g.stride_b;
+    const int block = g.block, unit = g.unit;
+    if (g.src_bf16) {
+        const uint16_t* src = reinterpret_cast<const uint16_t*>(g.src) + base;
+        for (int i = threadIdx.x; i < block; i += kSmallFwhtThreads) s_x[i] = bf16_to_f32(src[i * g.stride_e]);
+    } else {
+        const float* src = reinterpret_cast<const float*>(g.src) + base;
+        for (int i = threadIdx.x; i < block; i += kSmallFwhtThreads) s_x[i] = src[i * g.stride_e];
+    }
     __syncthreads();
-    const int p = block / unit;                          // length of the Walsh-Hadamard factor
+    const int p = g.log_p >= 0 ? 1 << g.log_p : 0;       // length of the Walsh-Hadamard factor
     if (unit == 28) {
-        for (int run = threadIdx.x; run < p; run += 256) {
+        for (int run = threadIdx.x; run < p; run += kSmallFwhtThreads) {
             float x[28], y[28];
 #pragma unroll
             for (int j = 0; j < 28; ++j) x[j] = s_x[run * 28 + j];
@@ -254,95 +371,133 @@ lr_row_fwht_kernel(const uint16_t* __restrict__ in, int64_t ld_in, float* __rest
         }
         __syncthreads();
     }
-    for (int h = 1; h < p; h <<= 1) {
-        for (int q = threadIdx.x; q < block / 2; q += 256) {
-            const int j = q % unit, ii = q / unit;
-            const int i = ((ii / h) * 2 * h) + (ii % h);
-            const float a = s_x[i * unit + j], b = s_x[(i + h) * unit + j];
-            s_x[i * unit + j] = a + b;
-            s_x[(i + h) * unit + j] = a - b;
+    for (int lh = 0; lh < g.log_p; ++lh) {
+        const int h = 1 << lh;
+        if (unit == 1) {
+            for (int ii = threadIdx.x; ii < (p >> 1); ii += kSmallFwhtThreads) {
+                const int i = ((ii >> lh) << (lh + 1)) | (ii & (h - 1));
+                const float a = s_x[i], b = s_x[i + h];
+                s_x[i] = a + b;
+                s_x[i + h] = a - b;
+            }
+        } else {
+            // pairs (ii, j): 28 consecutive threads share one ii
+            for (int q = threadIdx.x; q < (p >> 1) * 28; q += kSmallFwhtThreads) {
+                const int ii = q / 28, j = q - ii * 28;
+                const int i = ((ii >> lh) << (lh + 1)) | (ii & (h - 1));
+                const float a = s_x[i * 28 + j], b = s_x[(i + h) * 28 + j];
+                s_x[i * 28 + j] = a + b;
+                s_x[(i + h) * 28 + j] = a - b;
+            }
         }
         __syncthreads();
     }
-    float* dst = out + row * ld_out + base;
-    for (int i = threadIdx.x; i < block; i += 256) dst[i] = s_x[i] * c_norm;
+    float* dst = g.dst + va * g.dst_a + vb * g.dst_b;
+    for (int i = threadIdx.x; i < block; i += kSmallFwhtThreads) dst[i * g.dst_e] = s_x[i] * g.c_norm;
 }
 
-__global__ void __launch_bounds__(256)
-lr_widen_kernel(const uint16_t* __restrict__ in, int64_t ld_in, float* __restrict__ out, int64_t ld_out, int64_t cols) {
-    const int64_t row = blockIdx.y;
-    const int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (c < cols) out[row * ld_out + c] = bf16_to_f32(in[row * ld_in + c]);
+template <bool KMAJOR>
+hipError_t launch_down_by_rank(const uint16_t* in, int64_t ld_in, const uint16_t* bt, int64_t ld_b, float* out, int64_t rows,
+                               int64_t K, int rank, unsigned blocks, hipStream_t s) {
+    const dim3 grid(blocks), block(64 * kDownWaves);
+    if (rank <= 16)
+        hipLaunchKernelGGL((lr_down_kernel<1, KMAJOR>), grid, block, 0, s, in, ld_in, bt, ld_b, out, rows, K, rank);
+    else if (rank <= 32)
+        hipLaunchKernelGGL((lr_down_kernel<2, KMAJOR>), grid, block, 0, s, in, ld_in, bt, ld_b, out, rows, K, rank);
+    else
+        hipLaunchKernelGGL((lr_down_kernel<4, KMAJOR>), grid, block, 0, s, in, ld_in, bt, ld_b, out, rows, K, rank);
+    return hipGetLastError();
+}
+
+// Token ranges of the gradient kernel: enough workgroups to fill the chip, at least 64 tokens each, at most 16.
+int lr_grad_splits(int64_t rows, int64_t wide) {
+    const int64_t col_tiles = (wide + 127) / 128;
+    int64_t splits = (512 + col_tiles - 1) / col_tiles;
+    if (splits > kMaxGradSplits) splits = kMaxGradSplits;
+    const int64_t max_splits = (rows + 63) / 64;
+    if (splits > max_splits) splits = max_splits;
+    if (splits < 1) splits = 1;
+    return (int)splits;
+}
+
+bool fill_fwht_job(FwhtJob* j, const void* src, int src_bf16, float* dst, int64_t stride_a, int64_t stride_b, int64_t stride_e,
+                   int64_t count_a, int64_t count_b, int64_t block) {
+    j->src = src; j->dst = dst; j->src_bf16 = src_bf16;
+    j->stride_a = stride_a; j->stride_b = stride_b; j->stride_e = stride_e;
+    j->dst_a = stride_a; j->dst_b = stride_b; j->dst_e = stride_e;
+    if (count_a * count_b > (int64_t(1) << 24) || block > kSmallFwhtMax || block < 1) return false;
+    j->count_b = (int)count_b;
+    j->vectors = (int)(count_a * count_b);
+    j->block = (int)block;
+    const bool pow2 = (block & (block - 1)) == 0;
+    if (!pow2 && block % 28 != 0) return false;
+    j->unit = pow2 ? 1 : 28;
+    const int64_t p = block / j->unit;
+    if ((p & (p - 1)) != 0) return false;
+    j->log_p = 0;
+    while ((int64_t(1) << j->log_p) < p) ++j->log_p;
+    j->c_norm = (float)(1.0 / sqrt((double)block));
+    return true;
 }
 
 }  // namespace
 
 // ------------------------------------------------------------------------------------------------ launchers
-hipError_t launch_lr_down(const void* in, int64_t ld_in, const void* bt, int bt_is_f32, int64_t ld_b, float* out,
-                          int64_t rows, int64_t K, int rank, hipStream_t s) {
+hipError_t launch_lr_down(const void* in, int64_t ld_in, const void* thin, int k_major, int64_t ld_b, float* out, int64_t rows,
+                          int64_t K, int rank, hipStream_t s) {
     if (rows <= 0 || rank <= 0) return hipSuccess;
-    if (rank > kMaxLowRank || K % 32 != 0 || K <= 0 || ld_in < K || ld_b < K || ld_in % 8 != 0 ||
-        ld_b % (bt_is_f32 ? 4 : 8) != 0)
-        return hipErrorInvalidValue;
+    if (rank > kMaxLowRank || K % 64 != 0 || K <= 0 || ld_in < K || ld_in % 8 != 0) return hipErrorInvalidValue;
+    if (k_major ? ld_b < rank : (ld_b < K || ld_b % 8 != 0)) return hipErrorInvalidValue;
     const int64_t blocks = (rows + 15) / 16;
     if (blocks > 0x7FFFFFFF) return hipErrorInvalidValue;
-    if (bt_is_f32)
-        hipLaunchKernelGGL(lr_down_kernel<true>, dim3((unsigned)blocks), dim3(64 * kDownWaves), 0, s,
-                           reinterpret_cast<const uint16_t*>(in), ld_in, bt, ld_b, out, rows, K, rank);
-    else
-        hipLaunchKernelGGL(lr_down_kernel<false>, dim3((unsigned)blocks), dim3(64 * kDownWaves), 0, s,
-                           reinterpret_cast<const uint16_t*>(in), ld_in, bt, ld_b, out, rows, K, rank);
-    return hipGetLastError();
-}
-
-// Token ranges of the gradient kernel: enough workgroups to fill the chip, ranges a multiple of 16 tokens, at most 16.
-int lr_grad_splits(int64_t rows, int64_t wide) {
-    const int64_t col_tiles = (wide + 127) / 128;
-    int64_t splits = (768 + col_tiles - 1) / col_tiles;
-    if (splits > 16) splits = 16;
-    const int64_t max_splits = (rows + 63) / 64;         // at least 64 tokens per range
-    if (splits > max_splits) splits = max_splits;
-    if (splits < 1) splits = 1;
-    return (int)splits;
+    const uint16_t* a = reinterpret_cast<const uint16_t*>(in);
+    const uint16_t* b = reinterpret_cast<const uint16_t*>(thin);
+    return k_major ? launch_down_by_rank<true>(a, ld_in, b, ld_b, out, rows, K, rank, (unsigned)blocks, s)
+                   : launch_down_by_rank<false>(a, ld_in, b, ld_b, out, rows, K, rank, (unsigned)blocks, s);
 }
 
 size_t lr_grad_workspace_floats(int64_t rows, int64_t wide, int rank) {
     return (size_t)lr_grad_splits(rows, wide) * (size_t)wide * (size_t)rank;
 }
 
-hipError_t launch_lr_grad(const void* big, int64_t ld_big, const float* small, float* out, int transpose_out, float* part,
-                          int64_t rows, int64_t wide, int rank, hipStream_t s) {
-    if (wide <= 0 || rank <= 0) return hipSuccess;
-    if (rank > kMaxLowRank || wide % 8 != 0 || ld_big < wide || ld_big % 8 != 0 || rows <= 0) return hipErrorInvalidValue;
-    const int splits = lr_grad_splits(rows, wide);
-    int64_t per = (rows + splits - 1) / splits;
-    per = (per + 15) / 16 * 16;
-    const dim3 grid((unsigned)((wide + 127) / 128), (unsigned)splits);
-    const uint16_t* b16 = reinterpret_cast<const uint16_t*>(big);
-    if (rank <= 16)
-        hipLaunchKernelGGL(lr_grad_kernel<1>, grid, dim3(64 * kGradWaves), 0, s, b16, ld_big, small, part, rows, wide, rank, per);
-    else if (rank <= 32)
-        hipLaunchKernelGGL(lr_grad_kernel<2>, grid, dim3(64 * kGradWaves), 0, s, b16, ld_big, small, part, rows, wide, rank, per);
-    else
-        hipLaunchKernelGGL(lr_grad_kernel<4>, grid, dim3(64 * kGradWaves), 0, s, b16, ld_big, small, part, rows, wide, rank, per);
+hipError_t launch_lr_grads(const LrGradArgs* a, const LrGradArgs* b, int64_t rows, int rank, hipStream_t s) {
+    if (!a && !b) return hipSuccess;
+    if (!a) { a = b; b = nullptr; }
+    if (rank <= 0 || rank > kMaxLowRank || rank % 4 != 0 || rows <= 0) return hipErrorInvalidValue;
+    GradJob gj[2] = {};
+    ReduceJob rj[2] = {};
+    unsigned gx = 0, gy = 0;
+    int64_t rtotal = 0;
+    const LrGradArgs* src[2] = {a, b};
+    const int njobs = b ? 2 : 1;
+    for (int i = 0; i < njobs; ++i) {
+        const LrGradArgs& q = *src[i];
+        if (q.wide <= 0 || q.wide % 8 != 0 || q.ld_big < q.wide || q.ld_big % 8 != 0 || !q.big || !q.small || !q.out || !q.part)
+            return hipErrorInvalidValue;
+        const int splits = lr_grad_splits(rows, q.wide);
+        int64_t per = (rows + splits - 1) / splits;
+        per = (per + 15) / 16 * 16;
+        gj[i] = GradJob{reinterpret_cast<const uint16_t*>(q.big), q.ld_big, q.small, splits == 1 ? q.out : q.part, rows, q.wide,
+                        per, splits, q.transpose_out};
+        rj[i] = ReduceJob{q.part, q.out, q.wide * rank, splits};
+        const unsigned tiles = (unsigned)((q.wide + 127) / 128);
+        if (tiles > gx) gx = tiles;
+        if ((unsigned)splits > gy) gy = (unsigned)splits;
+        if (splits > 1 && q.wide * rank > rtotal) rtotal = q.wide * rank;
+    }
+    if (njobs == 1) gj[1] = gj[0], gj[1].splits = 0, rj[1] = rj[0], rj[1].splits = 0;
+    const dim3 grid(gx, gy, (unsigned)njobs), block(64 * kGradWaves);
+    if (rank <= 16) hipLaunchKernelGGL(lr_grad_kernel<1>, grid, block, 0, s, gj[0], gj[1], rank);
+    else if (rank <= 32) hipLaunchKernelGGL(lr_grad_kernel<2>, grid, block, 0, s, gj[0], gj[1], rank);
+    else hipLaunchKernelGGL(lr_grad_kernel<4>, grid, block, 0, s, gj[0], gj[1], rank);
     hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    const int64_t total = wide * rank;
-    hipLaunchKernelGGL(lr_reduce_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, part, out, wide, rank, splits,
-                       transpose_out);
-    return hipGetLastError();
-}
-
-hipError_t launch_lr_transpose(const void* in, float* out, int64_t n, int rank, hipStream_t s) {
-    if (n <= 0 || rank <= 0) return hipSuccess;
-    const int64_t total = n * rank;
-    hipLaunchKernelGGL(lr_transpose_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s,
-                       reinterpret_cast<const uint16_t*>(in), out, n, rank);
+    if (e != hipSuccess || rtotal == 0) return e;
+    hipLaunchKernelGGL(lr_reduce_kernel, dim3((unsigned)((rtotal / 4 + 255) / 256), (unsigned)njobs), dim3(256), 0, s, rj[0], rj[1]);
     return hipGetLastError();
 }
 
 bool lr_row_fwht_shape_ok(int64_t cols, int64_t block) {
-    if (block <= 1) return true;
+    if (block <= 1) return cols % 64 == 0;
     if (block > kSmallFwhtMax || cols % block != 0) return false;
     if ((block & (block - 1)) == 0) return true;
     if (block % 28 != 0) return false;
@@ -350,20 +505,33 @@ bool lr_row_fwht_shape_ok(int64_t cols, int64_t block) {
     return (p & (p - 1)) == 0;
 }
 
-hipError_t launch_lr_row_fwht(const void* in, int64_t ld_in, float* out, int64_t ld_out, int64_t rows, int64_t cols,
-                              int64_t block, hipStream_t s) {
-    if (rows <= 0 || cols <= 0) return hipSuccess;
-    if (!lr_row_fwht_shape_ok(cols, block) || rows > 65535) return hipErrorInvalidValue;
-    const uint16_t* src = reinterpret_cast<const uint16_t*>(in);
-    if (block <= 1) {
-        hipLaunchKernelGGL(lr_widen_kernel, dim3((unsigned)((cols + 255) / 256), (unsigned)rows), dim3(256), 0, s, src, ld_in,
-                           out, ld_out, cols);
-        return hipGetLastError();
+bool lr_col_fwht_shape_ok(int64_t rows, int64_t block) {
+    return block >= 2 && block <= kSmallFwhtMax && (block & (block - 1)) == 0 && rows % block == 0;
+}
+
+hipError_t launch_lr_rotations(const void* u, float* u_rot, int64_t rank, int64_t m, int64_t block_m, const float* sm,
+                               float* sm_rot, int64_t b, int64_t block_b, hipStream_t s) {
+    FwhtJob j[2] = {};
+    int n = 0;
+    if (u) {
+        if (!lr_row_fwht_shape_ok(m, block_m)) return hipErrorInvalidValue;
+        // rows of U [rank x m]: vector (row, block of the row); no rotation: blocks of 64, conversion only
+        const int64_t blk = block_m <= 1 ? 64 : block_m;
+        if (!fill_fwht_job(&j[n], u, 1, u_rot, m, blk, 1, rank, m / blk, blk)) return hipErrorInvalidValue;
+        if (block_m <= 1) { j[n].log_p = -1; j[n].c_norm = 1.0f; }
+        j[n].dst_a = 1; j[n].dst_b = blk * rank; j[n].dst_e = rank;      // transposed: element (col, r) at col * rank + r
+        ++n;
     }
-    const int unit = (block & (block - 1)) == 0 ? 1 : 28;
-    const float c_norm = (float)(1.0 / sqrt((double)block));
-    hipLaunchKernelGGL(lr_row_fwht_kernel, dim3((unsigned)(cols / block), (unsigned)rows), dim3(256), 0, s, src, ld_in, out,
-                       ld_out, (int)block, unit, c_norm);
+    if (sm) {
+        if (!lr_col_fwht_shape_ok(b, block_b)) return hipErrorInvalidValue;
+        // columns of S [b x rank]: vector (left block, column)
+        if (!fill_fwht_job(&j[n], sm, 0, sm_rot, block_b * rank, 1, rank, b / block_b, rank, block_b)) return hipErrorInvalidValue;
+        ++n;
+    }
+    if (n == 0) return hipSuccess;
+    if (n == 1) j[1] = j[0], j[1].vectors = 0;
+    hipLaunchKernelGGL(lr_small_fwht_kernel, dim3((unsigned)(j[0].vectors + j[1].vectors)), dim3(kSmallFwhtThreads), 0, s, j[0],
+                       j[1]);
     return hipGetLastError();
 }
 
