@@ -526,6 +526,11 @@ def main():
     torch.cuda.set_device(dev)
     assert len(inputs.CONFIGS[args.config].linears) == 1, "--config names a single-linear workload (c2, c3)"
 
+    if inputs.CONFIGS[args.config].peft_rank and not args.step_only:
+        print("bench.py: %s is reported under `configs` of the default run; alone it runs with --step-only" % args.config,
+              file=sys.stderr)
+        sys.exit(2)
+
     if args.pmc_target:
         pmc_run(args, dev)
         return
