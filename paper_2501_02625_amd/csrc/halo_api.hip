@@ -123,7 +123,7 @@ hipError_t finish_left_unrotation(float* t, int64_t b, int64_t m, int32_t hb, in
     r.in_mul = (float)(1.0 / sqrt((double)hb));
     set_right_block(r, hm);
     const OutKind ok = odt == HALO_BF16 ? OUT_BF16 : OUT_F32;
-    // up to four top strides left and a right-hand block of 512 .. 2048: one kernel does the rest
+    // up to four top strides left and a right-hand block of 512 .. 4096: one kernel does the rest
     const int top = ilog2_exact(hb) - 8;
     if (first_stage == 8 && r.kron_m == 0 && row_left_top_ok(b, m, r.log_block, top)) {
         r.left_top = top;

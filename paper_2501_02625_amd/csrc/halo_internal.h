@@ -52,7 +52,7 @@ hipError_t launch_row_transform(const RowArgs& a, InKind in, OutKind out, hipStr
 // The end of a left+right un-rotation in one kernel.  `in` is fp32 [rows x cols] on which all strides of a left-hand
 // rotation of block 256 << left_top have run except the top left_top ones; the kernel runs those (the 2^left_top rows
 // they mix sit in the wavefronts of one workgroup and meet in LDS), multiplies by in_mul, un-rotates each row in blocks
-// of 2^log_block and stores bf16 / fp32.  row_left_top_ok: the shapes it takes (log_block 9..11 dividing cols,
+// of 2^log_block and stores bf16 / fp32.  row_left_top_ok: the shapes it takes (log_block 9..12 dividing cols,
 // left_top 1..4, rows a multiple of the left block).
 bool row_left_top_ok(int64_t rows, int64_t cols, int log_block, int left_top);
 hipError_t launch_row_left_top(const RowArgs& a, OutKind out, hipStream_t s);

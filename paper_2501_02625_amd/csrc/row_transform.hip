@@ -540,7 +540,7 @@ hipError_t launch_by_seg(const RowArgs& a, hipStream_t s) {
 // lower row takes a + b, the upper one a - b), ascending; then the wavefront has its row of the left-rotated matrix in
 // registers, in the layout of the row kernel, and goes on as that kernel does.
 template <int LOGSEG, int OUT, int TOP>
-__global__ void __launch_bounds__(64 << TOP, 8)
+__global__ void __launch_bounds__(64 << TOP, LOGSEG >= 12 ? 4 : 8)
 row_left_top_kernel(RowArgs a, int segs, float c_norm) {
     constexpr int LOGE = 2, EPL = 4;
     constexpr int VPL = 1 << (LOGSEG - 6);
@@ -642,6 +642,7 @@ hipError_t launch_left_top_by_seg(const RowArgs& a, hipStream_t s) {
         case 9: return launch_left_top_by_top<9, OUT>(a, s);
         case 10: return launch_left_top_by_top<10, OUT>(a, s);
         case 11: return launch_left_top_by_top<11, OUT>(a, s);
+        case 12: return launch_left_top_by_top<12, OUT>(a, s);
         default: return hipErrorInvalidValue;
     }
 }
@@ -649,7 +650,7 @@ hipError_t launch_left_top_by_seg(const RowArgs& a, hipStream_t s) {
 }  // namespace
 
 bool row_left_top_ok(int64_t rows, int64_t cols, int log_block, int left_top) {
-    if (log_block < 9 || log_block > 11 || left_top < 1 || left_top > 4) return false;
+    if (log_block < 9 || log_block > 12 || left_top < 1 || left_top > 4) return false;
     if (rows <= 0 || cols <= 0 || cols % (int64_t(1) << log_block) != 0) return false;
     return rows % (int64_t(256) << left_top) == 0;
 }

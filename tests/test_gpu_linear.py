@@ -107,6 +107,9 @@ def test_small_layers_all_levels(b, m, n, level):
     (1024, 1536, 192, 512, 512, torch.float32),    # two left blocks of 512 (one top stride), three right blocks of 512
     (8192, 512, 64, 0, 0, torch.float32),          # left block 8192: five strides left, the strided pass takes them
     (768, 1024, 128, 0, 0, torch.float32),         # b = 3 * 256: left block 256, nothing left after the epilogue
+    (512, 4096, 64, 0, 0, torch.float32),          # one top stride, right block 4096 (64 values per lane)
+    (4096, 4096, 128, 0, 0, torch.bfloat16),       # four top strides, right block 4096
+    (2048, 8192, 64, 4096, 1024, torch.float32),   # two left blocks of 1024, two right blocks of 4096
 ])
 def test_level2_output_side_variants(b, m, n, hm, hb, odt):
     """Level 2 with the low left-hand strides in the product's epilogue: every way the rest of the un-rotation can go."""
