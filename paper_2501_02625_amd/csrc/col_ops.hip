@@ -21,10 +21,14 @@ static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 // ------------------------------------------------------------------------------------------------
 // One pass of the left-hand FWHT: stages with row strides 2^p .. 2^(p+LOGR-1), ascending.
 // A wavefront owns 64*CPL consecutive columns and the 2^LOGR rows  base + t*2^p.
-template <int LOGR, int CPL, int IN, int OUT>
+// SIDE (bf16 input, first pass only): the pass also accumulates, per column, the absolute maximum of in[r, k] * side_fold[r]
+// over all rows into side_amax (bit patterns of non-negative floats, atomic integer max; zeroed by the caller): what the
+// column quantiser of the same matrix needs, taken from the one read of it.
+template <int LOGR, int CPL, int IN, int OUT, bool SIDE = false>
 __global__ void __launch_bounds__(256)
 col_fwht_kernel(const void* in, int64_t ld_in, void* out, int64_t ld_out, int64_t rows, int64_t cols,
-                int p, float c_final, int64_t col_tiles, const float* row_scale, const float* post_scale) {
+                int p, float c_final, int64_t col_tiles, const float* row_scale, const float* post_scale,
+                const float* side_fold = nullptr, uint32_t* side_amax = nullptr) {
     constexpr int R = 1 << LOGR;
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
@@ -41,6 +45,9 @@ col_fwht_kernel(const void* in, int64_t ld_in, void* out, int64_t ld_out, int64_
     float my_scale = 1.0f;
     if constexpr (IN == IN_I32) {
         if (row_scale && lane < R) my_scale = row_scale[base + (int64_t)lane * stride];
+    }
+    if constexpr (SIDE) {
+        if (side_fold && lane < R) my_scale = side_fold[base + (int64_t)lane * stride];
     }
     if (col >= cols) return;
     const bool pair_ok = (CPL == 1) || (col + 1 < cols);
@@ -77,6 +84,21 @@ col_fwht_kernel(const void* in, int64_t ld_in, void* out, int64_t ld_out, int64_
                 v[t][0] = src[0];
             }
         }
+    }
+
+    if constexpr (SIDE) {
+        float mx[CPL];
+#pragma unroll
+        for (int c = 0; c < CPL; ++c) mx[c] = 0.0f;
+#pragma unroll
+        for (int t = 0; t < R; ++t) {
+            const float f = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(my_scale), t));
+#pragma unroll
+            for (int c = 0; c < CPL; ++c) mx[c] = fmaxf(mx[c], fabsf(v[t][c] * f));
+        }
+#pragma unroll
+        for (int c = 0; c < CPL; ++c)
+            if (col + c < cols && mx[c] > 0.0f) atomicMax(side_amax + col + c, __float_as_uint(mx[c]));
     }
 
     if constexpr (IN == IN_I32) {
@@ -161,6 +183,17 @@ hipError_t launch_pass(const void* in, int64_t ld_in, void* out, int64_t ld_out,
     if (blocks <= 0 || blocks > 0x7FFFFFFF) return hipErrorInvalidValue;
     hipLaunchKernelGGL((col_fwht_kernel<LOGR, CPL, IN, OUT>), dim3((unsigned)blocks), dim3(256), 0, s, in, ld_in,
                        out, ld_out, rows, cols, p, c_final, col_tiles, row_scale, post_scale);
+    return hipGetLastError();
+}
+
+// First pass with the side absmax: bf16 in, six stages, fp32 out.
+hipError_t launch_pass_side(const void* in, int64_t ld_in, void* out, int64_t ld_out, int64_t rows, int64_t cols, float c_final,
+                            hipStream_t s, const float* side_fold, uint32_t* side_amax) {
+    const int64_t col_tiles = (cols + 511) / 512;
+    const int64_t blocks = col_tiles * (rows >> 6);
+    if (blocks <= 0 || blocks > 0x7FFFFFFF) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((col_fwht_kernel<6, 2, IN_BF16, OUT_F32, true>), dim3((unsigned)blocks), dim3(256), 0, s, in, ld_in, out,
+                       ld_out, rows, cols, 0, c_final, col_tiles, nullptr, nullptr, side_fold, side_amax);
     return hipGetLastError();
 }
 
@@ -581,7 +614,11 @@ hipError_t launch_col_fwht(const ColFwhtArgs& a, hipStream_t s) {
         const OutKind ok = last ? a.out_kind : OUT_F32;
         const float cf = last ? c : 1.0f;
         hipError_t e;
-        if (ik == IN_BF16 && ok == OUT_F32)
+        if (first && a.side_amax) {
+            // only the shape the layer uses: bf16 in, a first pass of six stages from stage 0
+            if (ik != IN_BF16 || ok != OUT_F32 || sizes[i] != 6 || p != 0) return hipErrorInvalidValue;
+            e = launch_pass_side(src, ld_src, dst, ld_dst, a.rows, a.cols, cf, s, a.side_fold, a.side_amax);
+        } else if (ik == IN_BF16 && ok == OUT_F32)
             e = launch_pass_by_logr<IN_BF16, OUT_F32>(sizes[i], src, ld_src, dst, ld_dst, a.rows, a.cols, p, cf, s);
         else if (ik == IN_F32 && ok == OUT_F32)
             e = launch_pass_by_logr<IN_F32, OUT_F32>(sizes[i], src, ld_src, dst, ld_dst, a.rows, a.cols, p, cf, s);
@@ -677,6 +714,20 @@ hipError_t launch_col_quant_t_given(const ColQuantArgs& a, const float* given_am
     const dim3 g2((unsigned)((a.cols + kTJ - 1) / kTJ), (unsigned)((a.rows + kTI - 1) / kTI));
     hipLaunchKernelGGL(col_quant_t_kernel, g2, dim3(256), 0, s, reinterpret_cast<const uint16_t*>(a.in), a.ld_in,
                        a.rows, a.cols, a.fold, amax_bits, a.out_q, a.ld_q, a.out_scale);
+    return hipGetLastError();
+}
+
+hipError_t launch_zero_u32(uint32_t* p, int64_t n, hipStream_t s) {
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(fill_u32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, p, n, 0u);
+    return hipGetLastError();
+}
+
+hipError_t launch_col_quant_t_ready(const ColQuantArgs& a, hipStream_t s) {
+    if (a.rows == 0 || a.cols == 0) return hipSuccess;
+    const dim3 g2((unsigned)((a.cols + kTJ - 1) / kTJ), (unsigned)((a.rows + kTI - 1) / kTI));
+    hipLaunchKernelGGL(col_quant_t_kernel, g2, dim3(256), 0, s, reinterpret_cast<const uint16_t*>(a.in), a.ld_in,
+                       a.rows, a.cols, a.fold, reinterpret_cast<const uint32_t*>(a.amax_ws), a.out_q, a.ld_q, a.out_scale);
     return hipGetLastError();
 }
 

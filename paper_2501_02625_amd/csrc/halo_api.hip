@@ -654,15 +654,31 @@ halo_status halo_linear_bwd(const halo_linear_desc* desc, const void* E, const i
         st = halo_quant_dual(E, b, n, n, s_w, s_x, Eq, n, s_e, EqT, b, s_g, amax, halo_quant_dual_workspace_bytes(b, n), stream);
         if (st != HALO_OK) return st;
     } else {
-        if (EX) {
-            st = halo_hadamard_quant(E, HALO_BF16, b, n, n, HALO_QUANT_ROWS, 0, level >= 2 ? hb : 0, s_w, Eq, n, s_e, f32,
-                                     level >= 2 ? round256((size_t)b * n * 4) : 0, stream);
-            if (st != HALO_OK) return st;
-        }
-        if (G) {
-            st = halo_hadamard_quant(E, HALO_BF16, b, n, n, HALO_QUANT_COLS_T, 0, 0, s_x, EqT, b, s_g, amax,
-                                     round256((size_t)n * 4), stream);
-            if (st != HALO_OK) return st;
+        // Level 2, both products: the first strided pass of E's left-hand rotation reads all of E anyway and also
+        // takes the column maxima of E (x) s_x that the column quantiser needs (left blocks of at least 64 tokens).
+        const bool side = both && level >= 2 && hb >= 64;
+        if (side) {
+            uint32_t* amax_bits = reinterpret_cast<uint32_t*>(amax);
+            if (launch_zero_u32(amax_bits, n, hs) != hipSuccess) return HALO_EHIP;
+            ColFwhtArgs c{E, IN_BF16, n, f32, OUT_F32, n, f32, n, b, n, ilog2_exact(hb)};
+            c.side_fold = s_x; c.side_amax = amax_bits;
+            if (launch_col_fwht(c, hs) != hipSuccess) return HALO_EHIP;
+            RowArgs r{};
+            r.in = f32; r.ld_in = n; r.rows = b; r.cols = n; r.fold = s_w; r.out = Eq; r.ld_out = n; r.out_scale = s_e;
+            if (launch_row_transform(r, IN_F32, OUT_Q8, hs) != hipSuccess) return HALO_EHIP;
+            ColQuantArgs q{E, n, b, n, s_x, EqT, b, s_g, amax};
+            if (launch_col_quant_t_ready(q, hs) != hipSuccess) return HALO_EHIP;
+        } else {
+            if (EX) {
+                st = halo_hadamard_quant(E, HALO_BF16, b, n, n, HALO_QUANT_ROWS, 0, level >= 2 ? hb : 0, s_w, Eq, n, s_e, f32,
+                                         level >= 2 ? round256((size_t)b * n * 4) : 0, stream);
+                if (st != HALO_OK) return st;
+            }
+            if (G) {
+                st = halo_hadamard_quant(E, HALO_BF16, b, n, n, HALO_QUANT_COLS_T, 0, 0, s_x, EqT, b, s_g, amax,
+                                         round256((size_t)n * 4), stream);
+                if (st != HALO_OK) return st;
+            }
         }
     }
 

@@ -80,8 +80,14 @@ struct ColFwhtArgs {
     const float* post_scale;
     int first_stage;
     int skip_norm;
+    // side_amax != null (bf16 input, log_block >= 6, first_stage 0): the first pass also accumulates, per column, the
+    // absolute maximum of in[r, k] * side_fold[r] (side_fold may be null) over all rows into side_amax[cols], as bit
+    // patterns of non-negative floats; the caller zeroes it beforehand (launch_zero_u32).
+    const float* side_fold;
+    uint32_t* side_amax;
 };
 hipError_t launch_col_fwht(const ColFwhtArgs& a, hipStream_t s);
+hipError_t launch_zero_u32(uint32_t* p, int64_t n, hipStream_t s);
 
 // ---- column-wise absmax quantiser with transposed output (E^T)_Q ----
 struct ColQuantArgs {
@@ -95,6 +101,8 @@ struct ColQuantArgs {
     float* amax_ws;          // [cols] scratch: column absmax accumulated as bit patterns
 };
 hipError_t launch_col_quant_t(const ColQuantArgs& a, hipStream_t s);
+// The same with the columns' absolute maxima already in a.amax_ws (bit patterns, from the side output of launch_col_fwht).
+hipError_t launch_col_quant_t_ready(const ColQuantArgs& a, hipStream_t s);
 // The same with one given absmax (device scalar) for every column instead of the columns' own: the tensor-wide scale.
 hipError_t launch_col_quant_t_given(const ColQuantArgs& a, const float* given_amax, hipStream_t s);
 // out[0] = max(in[0..n-1]) (n >= 1, non-negative values).
