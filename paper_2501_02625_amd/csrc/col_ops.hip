@@ -52,27 +52,33 @@ col_fwht_kernel(const void* in, int64_t ld_in, void* out, int64_t ld_out, int64_
     if (col >= cols) return;
     const bool pair_ok = (CPL == 1) || (col + 1 < cols);
     float v[R][CPL];
+    // Every load is issued before the first use, with one branch around the whole set and none inside it (a branch per row
+    // makes the compiler wait for each load before it issues the next).
+    if constexpr (IN == IN_BF16) {
+        const uint16_t* src0 = reinterpret_cast<const uint16_t*>(in) + base * ld_in + col;
+        if (CPL == 2 && pair_ok) {
+            uint32_t w[R];
 #pragma unroll
-    for (int t = 0; t < R; ++t) {
-        const int64_t r = base + t * stride;
-        if constexpr (IN == IN_BF16) {
-            const uint16_t* src = reinterpret_cast<const uint16_t*>(in) + r * ld_in + col;
-            if constexpr (CPL == 2) {
-                if (pair_ok) {
-                    const uint32_t w = *reinterpret_cast<const uint32_t*>(src);
-                    v[t][0] = __uint_as_float(w << 16);
-                    v[t][1] = __uint_as_float(w & 0xFFFF0000u);
-                } else {
-                    v[t][0] = __uint_as_float((uint32_t)src[0] << 16);
-                    v[t][1] = 0.0f;
-                }
-            } else {
-                v[t][0] = __uint_as_float((uint32_t)src[0] << 16);
+            for (int t = 0; t < R; ++t) w[t] = *reinterpret_cast<const uint32_t*>(src0 + (int64_t)t * stride * ld_in);
+#pragma unroll
+            for (int t = 0; t < R; ++t) {
+                v[t][0] = __uint_as_float(w[t] << 16);
+                v[t][CPL - 1] = __uint_as_float(w[t] & 0xFFFF0000u);
             }
-        } else if constexpr (IN == IN_I32) {
-            // handled below: all loads first, then the conversion
         } else {
-            const float* src = reinterpret_cast<const float*>(in) + r * ld_in + col;
+            uint16_t w[R];
+#pragma unroll
+            for (int t = 0; t < R; ++t) w[t] = src0[(int64_t)t * stride * ld_in];
+#pragma unroll
+            for (int t = 0; t < R; ++t) {
+                if (CPL == 2) v[t][CPL - 1] = 0.0f;
+                v[t][0] = __uint_as_float((uint32_t)w[t] << 16);
+            }
+        }
+    } else if constexpr (IN == IN_F32) {
+#pragma unroll
+        for (int t = 0; t < R; ++t) {
+            const float* src = reinterpret_cast<const float*>(in) + (base + t * stride) * ld_in + col;
             if constexpr (CPL == 2) {
                 if (pair_ok) {
                     const float2 w = *reinterpret_cast<const float2*>(src);
@@ -151,25 +157,25 @@ col_fwht_kernel(const void* in, int64_t ld_in, void* out, int64_t ld_out, int64_
             for (int c = 0; c < CPL; ++c) v[t][c] *= c_final;
     }
 
+    if constexpr (OUT == OUT_F32) {
+        float* dst0 = reinterpret_cast<float*>(out) + base * ld_out + col;
+        if (CPL == 2 && pair_ok) {
 #pragma unroll
-    for (int t = 0; t < R; ++t) {
-        const int64_t r = base + t * stride;
-        if constexpr (OUT == OUT_F32) {
-            float* dst = reinterpret_cast<float*>(out) + r * ld_out + col;
-            if constexpr (CPL == 2) {
-                if (pair_ok) *reinterpret_cast<float2*>(dst) = make_float2(v[t][0], v[t][1]);
-                else dst[0] = v[t][0];
-            } else {
-                dst[0] = v[t][0];
-            }
+            for (int t = 0; t < R; ++t)
+                *reinterpret_cast<float2*>(dst0 + (int64_t)t * stride * ld_out) = make_float2(v[t][0], v[t][CPL - 1]);
         } else {
-            uint16_t* dst = reinterpret_cast<uint16_t*>(out) + r * ld_out + col;
-            if constexpr (CPL == 2) {
-                if (pair_ok) *reinterpret_cast<uint32_t*>(dst) = pack_bf16x2(v[t][0], v[t][1]);
-                else dst[0] = bf16_bits(v[t][0]);
-            } else {
-                dst[0] = bf16_bits(v[t][0]);
-            }
+#pragma unroll
+            for (int t = 0; t < R; ++t) dst0[(int64_t)t * stride * ld_out] = v[t][0];
+        }
+    } else {
+        uint16_t* dst0 = reinterpret_cast<uint16_t*>(out) + base * ld_out + col;
+        if (CPL == 2 && pair_ok) {
+#pragma unroll
+            for (int t = 0; t < R; ++t)
+                *reinterpret_cast<uint32_t*>(dst0 + (int64_t)t * stride * ld_out) = pack_bf16x2(v[t][0], v[t][CPL - 1]);
+        } else {
+#pragma unroll
+            for (int t = 0; t < R; ++t) dst0[(int64_t)t * stride * ld_out] = bf16_bits(v[t][0]);
         }
     }
 }
