@@ -316,31 +316,58 @@ col_quant_t_kernel(const uint16_t* in, int64_t ld_in, int64_t rows, int64_t cols
             inv[e] = am > 0.0f ? 127.0f / am : 0.0f;
             if (blockIdx.y == 0 && tid < 32 && col + e < cols) out_scale[col + e] = am > 0.0f ? am / 127.0f : 1.0f;
         }
-        const bool full = col + 4 <= cols;
+        // The 16 rows of this thread (4 quads of 4): all loads first.  A tile inside the matrix takes them with no branch in
+        // between (a branch per row makes the compiler wait for each load before it issues the next); a tile on the edge
+        // goes element by element.
+        uint2 w[4][4];
+        float f[4][4];
+        const bool interior = i0 + kTI <= rows && j0 + kTJ <= cols;
+        if (interior) {
+#pragma unroll
+            for (int s = 0; s < 4; ++s)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int64_t row = i0 + 4 * ((tid >> 5) + 8 * s) + r;
+                    w[s][r] = *reinterpret_cast<const uint2*>(in + row * ld_in + col);
+                }
+            if (fold) {
+#pragma unroll
+                for (int s = 0; s < 4; ++s)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) f[s][r] = fold[i0 + 4 * ((tid >> 5) + 8 * s) + r];
+            } else {
+#pragma unroll
+                for (int s = 0; s < 4; ++s)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) f[s][r] = 1.0f;
+            }
+        } else {
+#pragma unroll
+            for (int s = 0; s < 4; ++s)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int64_t row = i0 + 4 * ((tid >> 5) + 8 * s) + r;
+                    uint32_t h[4] = {0u, 0u, 0u, 0u};
+                    f[s][r] = 1.0f;
+                    if (row < rows) {
+                        if (fold) f[s][r] = fold[row];
+                        for (int e = 0; e < 4; ++e)
+                            if (col + e < cols) h[e] = in[row * ld_in + col + e];
+                    }
+                    w[s][r] = make_uint2(h[0] | (h[1] << 16), h[2] | (h[3] << 16));
+                }
+        }
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
             const int iq = (tid >> 5) + 8 * s;           // row quad inside the tile
             uint32_t b[4][4];                             // [row in quad][col]
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                const int64_t row = i0 + 4 * iq + r;
-                float x[4] = {0.f, 0.f, 0.f, 0.f};
-                float f = 1.0f;
-                if (row < rows && col < cols) {
-                    if (fold) f = fold[row];
-                    const uint16_t* src = in + row * ld_in + col;
-                    if (full) {
-                        const uint2 w = *reinterpret_cast<const uint2*>(src);
-                        x[0] = __uint_as_float(w.x << 16); x[1] = __uint_as_float(w.x & 0xFFFF0000u);
-                        x[2] = __uint_as_float(w.y << 16); x[3] = __uint_as_float(w.y & 0xFFFF0000u);
-                    } else {
-                        for (int e = 0; e < 4; ++e)
-                            if (col + e < cols) x[e] = __uint_as_float((uint32_t)src[e] << 16);
-                    }
-                }
+                const float x[4] = {__uint_as_float(w[s][r].x << 16), __uint_as_float(w[s][r].x & 0xFFFF0000u),
+                                    __uint_as_float(w[s][r].y << 16), __uint_as_float(w[s][r].y & 0xFFFF0000u)};
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    const float t = (x[e] * f) * inv[e];
+                    const float t = (x[e] * f[s][r]) * inv[e];
                     b[r][e] = __float_as_uint(t + 12582912.0f);
                 }
             }
