@@ -464,10 +464,37 @@ dual_amax_kernel(const uint16_t* __restrict__ in, int64_t ld_in, int64_t rows, i
     const int64_t col = (int64_t)blockIdx.x * kAC + 8 * jl;
     const int64_t row_base = (int64_t)blockIdx.y * (32 * ROUNDS) + 4 * rq;
     uint4 raw[ROUNDS][4];
+    float frow[ROUNDS][4];
+    // a tile inside the matrix takes its loads with no branch in between (a branch per load makes the compiler wait for
+    // each before it issues the next)
+    const bool interior = (int64_t)(blockIdx.y + 1) * (32 * ROUNDS) <= rows && (int64_t)(blockIdx.x + 1) * kAC <= cols;
+    if (interior) {
 #pragma unroll
-    for (int s = 0; s < ROUNDS; ++s)
+        for (int s = 0; s < ROUNDS; ++s)
 #pragma unroll
-        for (int r = 0; r < 4; ++r) raw[s][r] = load_row8(in, ld_in, rows, cols, row_base + 32 * s + r, col);
+            for (int r = 0; r < 4; ++r)
+                raw[s][r] = *reinterpret_cast<const uint4*>(in + (row_base + 32 * s + r) * ld_in + col);
+        if (fold_r) {
+#pragma unroll
+            for (int s = 0; s < ROUNDS; ++s)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) frow[s][r] = fold_r[row_base + 32 * s + r];
+        } else {
+#pragma unroll
+            for (int s = 0; s < ROUNDS; ++s)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) frow[s][r] = 1.0f;
+        }
+    } else {
+#pragma unroll
+        for (int s = 0; s < ROUNDS; ++s)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int64_t row = row_base + 32 * s + r;
+                raw[s][r] = load_row8(in, ld_in, rows, cols, row, col);
+                frow[s][r] = (fold_r && row < rows) ? fold_r[row] : 1.0f;
+            }
+    }
     float fc[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) fc[e] = (fold_c && col + e < cols) ? fold_c[col + e] : 1.0f;
@@ -477,7 +504,7 @@ dual_amax_kernel(const uint16_t* __restrict__ in, int64_t ld_in, int64_t rows, i
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const int64_t row = row_base + 32 * s + r;
-            const float fr = (fold_r && row < rows) ? fold_r[row] : 1.0f;
+            const float fr = frow[s][r];
             float x[8];
             widen_row8(raw[s][r], x);
             float rmax = 0.0f;
@@ -516,10 +543,35 @@ dual_quant_kernel(const uint16_t* __restrict__ in, int64_t ld_in, int64_t rows, 
     const int64_t col = j0 + 8 * jl;
     // E first (cache-hot after pass 1): all eight loads of the thread are in flight while the maxima are reduced.
     uint4 raw[2][4];
+    float frow[2][4];
+    const bool interior = i0 + kDR <= rows && j0 + kDC <= cols;
+    if (interior) {                        // no branch between the loads
 #pragma unroll
-    for (int s = 0; s < 2; ++s)
+        for (int s = 0; s < 2; ++s)
 #pragma unroll
-        for (int r = 0; r < 4; ++r) raw[s][r] = load_row8(in, ld_in, rows, cols, i0 + 4 * (rq + 16 * s) + r, col);
+            for (int r = 0; r < 4; ++r)
+                raw[s][r] = *reinterpret_cast<const uint4*>(in + (i0 + 4 * (rq + 16 * s) + r) * ld_in + col);
+        if (fold_r) {
+#pragma unroll
+            for (int s = 0; s < 2; ++s)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) frow[s][r] = fold_r[i0 + 4 * (rq + 16 * s) + r];
+        } else {
+#pragma unroll
+            for (int s = 0; s < 2; ++s)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) frow[s][r] = 1.0f;
+        }
+    } else {
+#pragma unroll
+        for (int s = 0; s < 2; ++s)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int64_t row = i0 + 4 * (rq + 16 * s) + r;
+                raw[s][r] = load_row8(in, ld_in, rows, cols, row, col);
+                frow[s][r] = (fold_r && row < rows) ? fold_r[row] : 1.0f;
+            }
+    }
     // Absmax of this tile's 128 columns and 128 rows from the partial maxima of pass 1 (every workgroup redoes the
     // reduction it needs: a few KB of L2 hits instead of one more kernel between the passes).
     {
@@ -568,7 +620,7 @@ dual_quant_kernel(const uint16_t* __restrict__ in, int64_t ld_in, int64_t rows, 
         for (int r = 0; r < 4; ++r) {
             const int64_t row = row0 + r;
             const bool rok = row < rows;
-            const float fr = (fold_r && rok) ? fold_r[row] : 1.0f;
+            const float fr = frow[s][r];
             const float am = s_amax_r[4 * iq + r];
             const float inv_r = am > 0.0f ? 127.0f / am : 0.0f;
             uint32_t br[8];
