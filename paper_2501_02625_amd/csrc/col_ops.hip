@@ -229,14 +229,11 @@ __global__ void __launch_bounds__(256) fill_u32_kernel(uint32_t* p, int64_t n, u
     if (i < n) p[i] = value;
 }
 
-__global__ void __launch_bounds__(256) fill_from_scalar_kernel(uint32_t* p, int64_t n, const float* value) {
-    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (i < n) p[i] = __float_as_uint(*value);
-}
-
 // out[0] = max over in[0..n-1]: one workgroup (the vectors reduced here are per-row maxima, a few thousand entries).
-__global__ void __launch_bounds__(1024) reduce_max_kernel(const float* in, int64_t n, float* out) {
+__global__ void __launch_bounds__(1024) reduce_max_kernel(const float* in, int64_t n, float* out, const float* in2, int64_t n2,
+                                                          float* out2) {
     __shared__ float s_part[16];
+    if (blockIdx.x == 1) { in = in2; n = n2; out = out2; }     // the second vector of a paired launch
     float m = 0.0f;
     for (int64_t i = threadIdx.x; i < n; i += 1024) m = fmaxf(m, in[i]);
 #pragma unroll
@@ -298,7 +295,7 @@ col_amax_kernel(const uint16_t* in, int64_t ld_in, int64_t rows, int64_t cols, c
 constexpr int kTI = 128, kTJ = 128, kPitch = kTI / 4 + 1;
 __global__ void __launch_bounds__(256)
 col_quant_t_kernel(const uint16_t* in, int64_t ld_in, int64_t rows, int64_t cols, const float* fold,
-                   const uint32_t* amax_bits, int8_t* out_q, int64_t ld_q, float* out_scale) {
+                   const uint32_t* amax_bits, int8_t* out_q, int64_t ld_q, float* out_scale, const float* given_amax = nullptr) {
     __shared__ uint32_t s_tile[kTJ * kPitch];
     const int tid = threadIdx.x;
     const int64_t j0 = (int64_t)blockIdx.x * kTJ;
@@ -312,7 +309,7 @@ col_quant_t_kernel(const uint16_t* in, int64_t ld_in, int64_t rows, int64_t cols
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             float am = 0.0f;
-            if (col + e < cols) am = __uint_as_float(amax_bits[col + e]);
+            if (col + e < cols) am = given_amax ? *given_amax : __uint_as_float(amax_bits[col + e]);   // one maximum for all columns
             inv[e] = am > 0.0f ? 127.0f / am : 0.0f;
             if (blockIdx.y == 0 && tid < 32 && col + e < cols) out_scale[col + e] = am > 0.0f ? am / 127.0f : 1.0f;
         }
@@ -783,22 +780,17 @@ hipError_t launch_dual_quant_static(DualQuantArgs a, hipStream_t s) {
     return launch_dual_quant(a, s);
 }
 
-hipError_t launch_reduce_max(const float* in, int64_t n, float* out, hipStream_t s) {
-    if (n <= 0) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(reduce_max_kernel, dim3(1), dim3(1024), 0, s, in, n, out);
+hipError_t launch_reduce_max(const float* in, int64_t n, float* out, hipStream_t s, const float* in2, int64_t n2, float* out2) {
+    if (n <= 0 || (in2 && n2 <= 0)) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(reduce_max_kernel, dim3(in2 ? 2 : 1), dim3(1024), 0, s, in, n, out, in2, n2, out2);
     return hipGetLastError();
 }
 
 hipError_t launch_col_quant_t_given(const ColQuantArgs& a, const float* given_amax, hipStream_t s) {
     if (a.rows == 0 || a.cols == 0) return hipSuccess;
-    uint32_t* amax_bits = reinterpret_cast<uint32_t*>(a.amax_ws);
-    hipLaunchKernelGGL(fill_from_scalar_kernel, dim3((unsigned)((a.cols + 255) / 256)), dim3(256), 0, s, amax_bits, a.cols,
-                       given_amax);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
     const dim3 g2((unsigned)((a.cols + kTJ - 1) / kTJ), (unsigned)((a.rows + kTI - 1) / kTI));
     hipLaunchKernelGGL(col_quant_t_kernel, g2, dim3(256), 0, s, reinterpret_cast<const uint16_t*>(a.in), a.ld_in,
-                       a.rows, a.cols, a.fold, amax_bits, a.out_q, a.ld_q, a.out_scale);
+                       a.rows, a.cols, a.fold, static_cast<const uint32_t*>(nullptr), a.out_q, a.ld_q, a.out_scale, given_amax);
     return hipGetLastError();
 }
 

@@ -101,7 +101,7 @@ BwdWorkspace bwd_layout(const halo_linear_desc* d) {
     w.tq = off;                                     // scratch of the one-scale-per-tensor quantiser (without its left part)
     if (d->scale_mode == HALO_SCALE_PER_TENSOR) {
         const size_t longest = b > n ? b : n;
-        off += round256((longest + 64) * 4) + round256(n * 4);
+        off += round256((longest + 64) * 4) + round256(n * 4) + 1024;       // + a second vector's maximum (forward: X and W)
     }
     w.total = off;
     return w;
@@ -546,6 +546,25 @@ halo_status halo_linear_fwd(const halo_linear_desc* desc, const void* X, const v
         if (!aligned16(workspace)) return HALO_EALIGN;
         unsigned char* tq = reinterpret_cast<unsigned char*>(workspace) + L.tq;
         const size_t tq_bytes = L.total - L.tq;
+        if (X && W) {
+            // X and W get the same treatment: one launch for the row maxima of both, one for the two tensor maxima, one
+            // that rotates again and quantises both
+            hipStream_t hs = reinterpret_cast<hipStream_t>(stream);
+            float* row_max_x = reinterpret_cast<float*>(tq);
+            float* row_max_w = row_max_x + b;
+            float* tmax = row_max_w + n;                       // two maxima, 64 floats apart
+            if (tq_bytes < (size_t)(b + n + 128) * 4) return HALO_EWORKSPACE;
+            RowArgs r{};
+            r.in = X; r.ld_in = m; r.rows = b; r.cols = m; r.out = Xq; r.ld_out = m; r.out_scale = row_max_x;
+            set_right_block(r, hm);
+            r.rows2 = n; r.in2 = W; r.out2 = Wq; r.out_scale2 = row_max_w;
+            r.amax_only = 1;
+            if (launch_row_transform(r, IN_BF16, OUT_Q8, hs) != hipSuccess) return HALO_EHIP;
+            if (launch_reduce_max(row_max_x, b, tmax, hs, row_max_w, n, tmax + 64) != hipSuccess) return HALO_EHIP;
+            r.amax_only = 0; r.given_amax = tmax; r.given_amax2 = tmax + 64; r.out_scale = s_x; r.out_scale2 = s_w;
+            if (launch_row_transform(r, IN_BF16, OUT_Q8, hs) != hipSuccess) return HALO_EHIP;
+            return halo_gemm_i8(Xq, m, Wq, m, 1, b, n, m, s_x, s_w, Y, odt, n, nullptr, 0, stream);
+        }
         if (X) {
             st = halo_hadamard_quant_tensor(X, HALO_BF16, b, m, m, HALO_QUANT_ROWS, hm, 0, Xq, m, s_x, tq, tq_bytes, stream);
             if (st != HALO_OK) return st;
@@ -611,6 +630,31 @@ halo_status halo_linear_bwd(const halo_linear_desc* desc, const void* E, const i
         // 2), and E's scale and the saved tensor's scale multiply the accumulators afterwards, in that order.
         unsigned char* tq = ws + L.tq;
         const size_t tq_bytes = L.total - L.tq;
+        if (both && level <= 1) {
+            // No left-hand rotation: both quantisations of E share the tensor's maximum.  One absmax pass and one reduction,
+            // then the row and the (transposed) column quantiser with that maximum, both products in one launch, both
+            // un-rotations in one launch.
+            if (tq_bytes < round256(((size_t)b + 64) * 4) + round256((size_t)n * 4)) return HALO_EWORKSPACE;
+            float* row_max = reinterpret_cast<float*>(tq);
+            float* tmax = row_max + b;
+            float* col_ws = reinterpret_cast<float*>(tq + round256(((size_t)b + 64) * 4));
+            RowArgs r{};
+            r.in = E; r.ld_in = n; r.rows = b; r.cols = n; r.out = Eq; r.ld_out = n; r.out_scale = row_max; r.amax_only = 1;
+            if (launch_row_transform(r, IN_BF16, OUT_Q8, hs) != hipSuccess) return HALO_EHIP;
+            if (launch_reduce_max(row_max, b, tmax, hs) != hipSuccess) return HALO_EHIP;
+            r.amax_only = 0; r.given_amax = tmax; r.out_scale = s_e;
+            if (launch_row_transform(r, IN_BF16, OUT_Q8, hs) != hipSuccess) return HALO_EHIP;
+            ColQuantArgs q{E, n, b, n, nullptr, EqT, b, s_g, col_ws};
+            if (launch_col_quant_t_given(q, tmax, hs) != hipSuccess) return HALO_EHIP;
+            GemmArgs gx{Eq, n, Wq, m, 0, b, m, n, nullptr, nullptr, nullptr, 0, m, acc, m, HALO_GEMM_AUTO};
+            GemmArgs gg{EqT, b, Xq, m, 0, n, m, b, nullptr, nullptr, nullptr, 0, m, acc_g, m, HALO_GEMM_AUTO};
+            if (launch_gemm_i8_pair(gx, gg, hs) != hipSuccess) return HALO_EHIP;
+            RowArgs u{};
+            u.in = acc; u.ld_in = m; u.rows = b; u.cols = m; u.pre_scale = s_e; u.post_scale = s_w; u.out = EX; u.ld_out = m;
+            set_right_block(u, level >= 1 ? hm : 0);
+            u.rows2 = n; u.in2 = acc_g; u.pre_scale2 = s_g; u.post_scale2 = s_x; u.out2 = G;
+            return from_hip(launch_row_transform(u, IN_I32, odt == HALO_BF16 ? OUT_BF16 : OUT_F32, hs));
+        }
         // The left-rotated copy of E is made here, in the layer's fp32 scratch, and handed to the quantiser as fp32
         // input (the un-rotation reuses that scratch afterwards).
         if (EX) {

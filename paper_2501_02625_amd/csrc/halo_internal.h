@@ -43,6 +43,8 @@ struct RowArgs {
     const float* pre_scale2;
     void* out2;
     float* out_scale2;
+    const float* given_amax2;    // the second matrix's own given_amax / post_scale; null: those of the first
+    const float* post_scale2;
 };
 // Largest row length the row kernels accept.
 constexpr int64_t kMaxRowCols = 32768;
@@ -105,8 +107,9 @@ hipError_t launch_col_quant_t(const ColQuantArgs& a, hipStream_t s);
 hipError_t launch_col_quant_t_ready(const ColQuantArgs& a, hipStream_t s);
 // The same with one given absmax (device scalar) for every column instead of the columns' own: the tensor-wide scale.
 hipError_t launch_col_quant_t_given(const ColQuantArgs& a, const float* given_amax, hipStream_t s);
-// out[0] = max(in[0..n-1]) (n >= 1, non-negative values).
-hipError_t launch_reduce_max(const float* in, int64_t n, float* out, hipStream_t s);
+// out[0] = max(in[0..n-1]) (n >= 1, non-negative values).  With in2: out2[0] = max(in2[0..n2-1]) in the same launch.
+hipError_t launch_reduce_max(const float* in, int64_t n, float* out, hipStream_t s, const float* in2 = nullptr,
+                             int64_t n2 = 0, float* out2 = nullptr);
 
 // ---- both quantisations of E for the backward pass from one tiling (rows for E_X, transposed columns for G) ----
 struct DualQuantArgs {

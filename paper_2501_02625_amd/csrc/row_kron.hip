@@ -105,6 +105,8 @@ row_kron28_kernel(RowArgs a, float c_norm, unsigned blocks1) {
     if (block >= blocks1) {                  // the second matrix of a batched launch
         block -= blocks1;
         a.in = a.in2; a.pre_scale = a.pre_scale2; a.out = a.out2; a.out_scale = a.out_scale2; a.rows = a.rows2;
+        if (a.given_amax2) a.given_amax = a.given_amax2;
+        if (a.post_scale2) a.post_scale = a.post_scale2;
     }
     const int64_t row = block;               // the grid holds exactly one workgroup per row
     const int64_t k0 = (int64_t)tid * kM;

@@ -433,6 +433,8 @@ row_transform_kernel(RowArgs a, int segs, int rows_per_wg, float c_norm, unsigne
     if (block >= blocks1) {          // the second matrix of a batched launch
         block -= blocks1;
         a.in = a.in2; a.pre_scale = a.pre_scale2; a.out = a.out2; a.out_scale = a.out_scale2; a.rows = a.rows2;
+        if (a.given_amax2) a.given_amax = a.given_amax2;
+        if (a.post_scale2) a.post_scale = a.post_scale2;
     }
     x.row = (int64_t)block * rows_per_wg + row_local;
     x.row_ok = x.row < a.rows;
