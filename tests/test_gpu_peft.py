@@ -117,6 +117,9 @@ SHAPES = [
     (96, 192, 64, 24, 2, 64, 32),          # rank 24 (a masked half tile), small blocks
     (256, 1792, 256, 16, 2, 1792, 256),    # Kronecker rotation H_64 (x) H_28
     (2048, 4096, 4096, 16, 2, 0, 0),       # 256x128 forward tiles, 256x256 backward tiles, four top left strides
+    (32768, 64, 64, 8, 2, 64, 32768),      # left block too long for the small rotation kernel: strided passes for H S
+    (512, 14336, 128, 16, 2, 14336, 512),  # one Kronecker block H_512 (x) H_28 over 14336
+    (1024, 2048, 192, 64, 2, 2048, 1024),  # rank 64 (four rank tiles), right block 2048
 ]
 
 
