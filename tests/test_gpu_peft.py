@@ -4,7 +4,7 @@ The quantised branch keeps the bars of the plain layer (with a zero adapter the 
 oracle's).  The low-rank branch is floating point accumulated in fp32 in an order the hardware picks, against exact
 products in the oracle, so it is compared within bounds derived from the arithmetic, u = 2^-24:
   T = X U^T, S = E V          |err| <= (16 + K/16) u (|X| |U|^T)          K = m resp. n (one matrix instruction per 32 terms)
-  G_V, G_U                    |err| <= (32 + b/4) u (|E|^T |T|) ...        (one matrix instruction per 4 tokens)
+  G_V, G_U                    |err| <= (32 + b/4) u (|E|^T |T|) ...        (a generous count: one rounding per 4 tokens)
   Y                           |err| <= (32 + m/16) u (|Y_q| + (|X||U|^T)|V|^T)
   E_X                         the same with n, plus 64 u (max|E_X,q| + max|S U|): the low-rank term is added before the
                               un-rotation, whose fp32 roundings then act on the sum
