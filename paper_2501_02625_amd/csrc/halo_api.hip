@@ -839,21 +839,20 @@ halo_status halo_peft_bwd(const halo_linear_desc* desc, int32_t rank, const void
 
     // ---- the thin products: S = E V, G_V = E^T T, G_U = S^T X
     if ((EX || GU) && launch_lr_down(E, n, V, 1, rank, S, b, n, rank, hs) != hipSuccess) return HALO_EHIP;
-    {
-        const LrGradArgs gv{E, n, T, GV, 0, part, n}, gu{X, m, S, GU, 1, part_u, m};
-        if (launch_lr_grads(GV ? &gv : nullptr, GU ? &gu : nullptr, b, rank, hs) != hipSuccess) return HALO_EHIP;
-    }
-    if (!EX) return HALO_OK;
-
-    // ---- E_X = S U + [un-rotation of the quantised product].  The low-rank term joins the product before the
-    // un-rotation, in the rotated domain: (H_left S) (U H_right), added to the scaled accumulators in the GEMM epilogue;
-    // the un-rotation of the sum then returns S U next to the quantised term (the rotations are orthogonal).
+    // E_X = S U + [un-rotation of the quantised product].  The low-rank term joins the product before the un-rotation,
+    // in the rotated domain: (H_left S) (U H_right), added to the scaled accumulators in the GEMM epilogue; the un-rotation
+    // of the sum then returns S U next to the quantised term (the rotations are orthogonal).
     const float* lr_a = S;
-    const bool rotate_s = level >= 2;
+    const bool rotate_s = EX && level >= 2;
     const bool s_small = rotate_s && lr_col_fwht_shape_ok(b, hb);
     if (rotate_s) lr_a = Sp;
-    if (launch_lr_rotations(U, Up, rank, m, level >= 1 ? hm : 0, s_small ? S : nullptr, Sp, b, hb, hs) != hipSuccess)
-        return HALO_EHIP;
+    {
+        const LrGradArgs gv{E, n, T, GV, 0, part, n}, gu{X, m, S, GU, 1, part_u, m};
+        const LrRotArgs rot{U, Up, m, level >= 1 ? hm : 0, s_small ? S : nullptr, Sp, b, hb};
+        if (launch_lr_backward_small(GV ? &gv : nullptr, GU ? &gu : nullptr, b, rank, EX ? &rot : nullptr, hs) != hipSuccess)
+            return HALO_EHIP;
+    }
+    if (!EX) return HALO_OK;
     if (rotate_s && !s_small) {            // left blocks too long for one workgroup's LDS: the strided passes
         ColFwhtArgs c{S, IN_F32, rank, Sp, OUT_F32, rank, Sp, rank, b, rank, ilog2_exact(hb)};
         if (launch_col_fwht(c, hs) != hipSuccess) return HALO_EHIP;

@@ -178,8 +178,7 @@ hipError_t launch_mfma_i8_probe(const int8_t* operands, int iters, int32_t* sink
 hipError_t launch_lr_down(const void* in, int64_t ld_in, const void* thin, int k_major, int64_t ld_b, float* out, int64_t rows,
                           int64_t K, int rank, hipStream_t s);
 // out = big^T small: big bf16 [rows x wide], small fp32 [rows x rank] dense; out fp32 [wide x rank], or its transpose
-// [rank x wide] with transpose_out.  part: lr_grad_workspace_floats(rows, wide, rank) floats of scratch.  Two such
-// products over the same rows ride in one launch (either pointer may be null).
+// [rank x wide] with transpose_out.  part: lr_grad_workspace_floats(rows, wide, rank) floats of scratch.
 struct LrGradArgs {
     const void* big;
     int64_t ld_big;
@@ -190,14 +189,23 @@ struct LrGradArgs {
     int64_t wide;
 };
 size_t lr_grad_workspace_floats(int64_t rows, int64_t wide, int rank);
-hipError_t launch_lr_grads(const LrGradArgs* a, const LrGradArgs* b, int64_t rows, int rank, hipStream_t s);
-// The rotated forms of the thin operands of the E_X epilogue, one launch:  u_rot fp32 [m x rank] = the TRANSPOSE of u bf16
+// The rotated forms of the thin operands of the E_X epilogue:  u_rot fp32 [m x rank] = the TRANSPOSE of u bf16
 // [rank x m] with every row rotated in blocks of block_m (2^n, or 28 * 2^n; <= 1: only widened), and sm_rot fp32
 // [b x rank] = sm fp32 [b x rank] with every column rotated in blocks of block_b (a power of two).  Either pair may be null.
+struct LrRotArgs {
+    const void* u;
+    float* u_rot;
+    int64_t m, block_m;
+    const float* sm;
+    float* sm_rot;
+    int64_t b, block_b;
+};
 bool lr_row_fwht_shape_ok(int64_t cols, int64_t block);
 bool lr_col_fwht_shape_ok(int64_t rows, int64_t block);
-hipError_t launch_lr_rotations(const void* u, float* u_rot, int64_t rank, int64_t m, int64_t block_m, const float* sm,
-                               float* sm_rot, int64_t b, int64_t block_b, hipStream_t s);
+// Everything small of the backward pass of the low-rank branch in two launches: the gradient products a and b (either or
+// both may be null), then the sums over their token ranges together with the rotations `rot` (may be null).
+hipError_t launch_lr_backward_small(const LrGradArgs* a, const LrGradArgs* b, int64_t rows, int rank, const LrRotArgs* rot,
+                                    hipStream_t s);
 
 // ---- MXFP6 GEMM: C[M x N] = A[M x K] B[N x K]^T on packed E3M2 codes with one E8M0 scale per 32 elements along K ----
 struct Mx6GemmArgs {

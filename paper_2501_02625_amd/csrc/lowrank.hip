@@ -1,7 +1,7 @@
 // The high-precision low-rank side branch of a LoRA-style linear module next to the quantised products (Section 3.3
 // "Parameter Efficient Fine Tuning"; Appendix "LoRA-style Linear Module and HALO for PEFT"):
 //   T = X U^T,  S = E_Y V            (tall input times a thin matrix: lr_down_kernel, bf16 matrix instructions)
-//   G_V = E_Y^T T,  G_U = S^T X      (thin result, reduction over the tokens: lr_grad_kernel + lr_reduce_kernel)
+//   G_V = E_Y^T T,  G_U = S^T X      (thin result, reduction over the tokens: lr_grad_kernel, summed up in lr_tail_kernel)
 // and the small helpers that bring V and U into the form the GEMM epilogue wants (rank-major; U rotated).  The additions
 // T V^T and S U themselves happen in the epilogue of the INT8 GEMM.  All inputs are bf16, every product accumulates in
 // fp32 and the intermediates T and S stay fp32.  Every kernel here is bound by one read of its tall operand from HBM.
@@ -258,7 +258,7 @@ lr_grad_kernel(GradJob j0, GradJob j1, int rank) {
 }
 
 // out[i] = sum over the splits of part[s][i], in order; four consecutive elements per thread (total a multiple of 4).
-// All partial sums are fetched before the first addition (absent ones count as zero).  blockIdx.y picks the job.
+// All partial sums are fetched before the first addition (absent ones count as zero).
 struct ReduceJob {
     const float* part;
     float* out;
@@ -267,10 +267,10 @@ struct ReduceJob {
 };
 constexpr int kMaxGradSplits = 16;
 
-__global__ void __launch_bounds__(256)
-lr_reduce_kernel(ReduceJob r0, ReduceJob r1) {
-    const ReduceJob& r = blockIdx.y == 0 ? r0 : r1;
-    const int64_t idx = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
+constexpr int kTailThreads = 1024;
+
+__device__ __forceinline__ void lr_reduce_body(const ReduceJob& r, int blk) {
+    const int64_t idx = ((int64_t)blk * kTailThreads + threadIdx.x) * 4;
     if (idx >= r.total || r.splits <= 1) return;
     float4 p[kMaxGradSplits];
 #pragma unroll
@@ -321,7 +321,7 @@ __device__ const H28Rows kH28Rows = make_h28_rows();
 // job's vectors come first in the grid.  The order of the additions is not that of the row kernels; nothing here needs to
 // be reproducible to the bit against a reference.  Used for U H (rows of the adapter U) and H S (columns of S = E V).
 constexpr int kSmallFwhtMax = 16384;
-constexpr int kSmallFwhtThreads = 1024;
+constexpr int kSmallFwhtThreads = kTailThreads;
 
 struct FwhtJob {
     const void* src;
@@ -335,12 +335,21 @@ struct FwhtJob {
     float c_norm;
 };
 
-__global__ void __launch_bounds__(kSmallFwhtThreads)
-lr_small_fwht_kernel(FwhtJob j0, FwhtJob j1) {
+// The small work at the end of the thin backward products, one launch: the first nb0 + nb1 workgroups add up the token
+// ranges of the two adapter gradients (lr_reduce_body), the others each rotate one vector.
+__global__ void __launch_bounds__(kTailThreads)
+lr_tail_kernel(ReduceJob r0, ReduceJob r1, int nb0, int nb1, FwhtJob j0, FwhtJob j1) {
     __shared__ float s_x[kSmallFwhtMax];
-    const bool first = (int)blockIdx.x < j0.vectors;
+    int blk = blockIdx.x;
+    if (blk < nb0 + nb1) {                 // uniform over the workgroup
+        if (blk < nb0) lr_reduce_body(r0, blk);
+        else lr_reduce_body(r1, blk - nb0);
+        return;
+    }
+    blk -= nb0 + nb1;
+    const bool first = blk < j0.vectors;
     const FwhtJob& g = first ? j0 : j1;
-    const int vec = first ? (int)blockIdx.x : (int)blockIdx.x - j0.vectors;
+    const int vec = first ? blk : blk - j0.vectors;
     const int64_t va = vec / g.count_b, vb = vec % g.count_b;
     const int64_t base = va * g.stride_a + vb * g.stride_b;
     const int block = g.block, unit = g.unit;
@@ -460,42 +469,6 @@ size_t lr_grad_workspace_floats(int64_t rows, int64_t wide, int rank) {
     return (size_t)lr_grad_splits(rows, wide) * (size_t)wide * (size_t)rank;
 }
 
-hipError_t launch_lr_grads(const LrGradArgs* a, const LrGradArgs* b, int64_t rows, int rank, hipStream_t s) {
-    if (!a && !b) return hipSuccess;
-    if (!a) { a = b; b = nullptr; }
-    if (rank <= 0 || rank > kMaxLowRank || rank % 4 != 0 || rows <= 0) return hipErrorInvalidValue;
-    GradJob gj[2] = {};
-    ReduceJob rj[2] = {};
-    unsigned gx = 0, gy = 0;
-    int64_t rtotal = 0;
-    const LrGradArgs* src[2] = {a, b};
-    const int njobs = b ? 2 : 1;
-    for (int i = 0; i < njobs; ++i) {
-        const LrGradArgs& q = *src[i];
-        if (q.wide <= 0 || q.wide % 8 != 0 || q.ld_big < q.wide || q.ld_big % 8 != 0 || !q.big || !q.small || !q.out || !q.part)
-            return hipErrorInvalidValue;
-        const int splits = lr_grad_splits(rows, q.wide);
-        int64_t per = (rows + splits - 1) / splits;
-        per = (per + 15) / 16 * 16;
-        gj[i] = GradJob{reinterpret_cast<const uint16_t*>(q.big), q.ld_big, q.small, splits == 1 ? q.out : q.part, rows, q.wide,
-                        per, splits, q.transpose_out};
-        rj[i] = ReduceJob{q.part, q.out, q.wide * rank, splits};
-        const unsigned tiles = (unsigned)((q.wide + 127) / 128);
-        if (tiles > gx) gx = tiles;
-        if ((unsigned)splits > gy) gy = (unsigned)splits;
-        if (splits > 1 && q.wide * rank > rtotal) rtotal = q.wide * rank;
-    }
-    if (njobs == 1) gj[1] = gj[0], gj[1].splits = 0, rj[1] = rj[0], rj[1].splits = 0;
-    const dim3 grid(gx, gy, (unsigned)njobs), block(64 * kGradWaves);
-    if (rank <= 16) hipLaunchKernelGGL(lr_grad_kernel<1>, grid, block, 0, s, gj[0], gj[1], rank);
-    else if (rank <= 32) hipLaunchKernelGGL(lr_grad_kernel<2>, grid, block, 0, s, gj[0], gj[1], rank);
-    else hipLaunchKernelGGL(lr_grad_kernel<4>, grid, block, 0, s, gj[0], gj[1], rank);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess || rtotal == 0) return e;
-    hipLaunchKernelGGL(lr_reduce_kernel, dim3((unsigned)((rtotal / 4 + 255) / 256), (unsigned)njobs), dim3(256), 0, s, rj[0], rj[1]);
-    return hipGetLastError();
-}
-
 bool lr_row_fwht_shape_ok(int64_t cols, int64_t block) {
     if (block <= 1) return cols % 64 == 0;
     if (block > kSmallFwhtMax || cols % block != 0) return false;
@@ -509,29 +482,69 @@ bool lr_col_fwht_shape_ok(int64_t rows, int64_t block) {
     return block >= 2 && block <= kSmallFwhtMax && (block & (block - 1)) == 0 && rows % block == 0;
 }
 
-hipError_t launch_lr_rotations(const void* u, float* u_rot, int64_t rank, int64_t m, int64_t block_m, const float* sm,
-                               float* sm_rot, int64_t b, int64_t block_b, hipStream_t s) {
-    FwhtJob j[2] = {};
-    int n = 0;
-    if (u) {
-        if (!lr_row_fwht_shape_ok(m, block_m)) return hipErrorInvalidValue;
-        // rows of U [rank x m]: vector (row, block of the row); no rotation: blocks of 64, conversion only
-        const int64_t blk = block_m <= 1 ? 64 : block_m;
-        if (!fill_fwht_job(&j[n], u, 1, u_rot, m, blk, 1, rank, m / blk, blk)) return hipErrorInvalidValue;
-        if (block_m <= 1) { j[n].log_p = -1; j[n].c_norm = 1.0f; }
-        j[n].dst_a = 1; j[n].dst_b = blk * rank; j[n].dst_e = rank;      // transposed: element (col, r) at col * rank + r
-        ++n;
+hipError_t launch_lr_backward_small(const LrGradArgs* a, const LrGradArgs* b, int64_t rows, int rank, const LrRotArgs* rot,
+                                    hipStream_t s) {
+    if (rank <= 0 || rank > kMaxLowRank || rank % 4 != 0 || rows <= 0) return hipErrorInvalidValue;
+    if (!a) { a = b; b = nullptr; }
+    // ---- the gradient products, one launch
+    GradJob gj[2] = {};
+    ReduceJob rj[2] = {};
+    int nb[2] = {0, 0};
+    if (a) {
+        unsigned gx = 0, gy = 0;
+        const LrGradArgs* src[2] = {a, b};
+        const int njobs = b ? 2 : 1;
+        for (int i = 0; i < njobs; ++i) {
+            const LrGradArgs& q = *src[i];
+            if (q.wide <= 0 || q.wide % 8 != 0 || q.ld_big < q.wide || q.ld_big % 8 != 0 || !q.big || !q.small || !q.out ||
+                !q.part)
+                return hipErrorInvalidValue;
+            const int splits = lr_grad_splits(rows, q.wide);
+            int64_t per = (rows + splits - 1) / splits;
+            per = (per + 15) / 16 * 16;
+            gj[i] = GradJob{reinterpret_cast<const uint16_t*>(q.big), q.ld_big, q.small, splits == 1 ? q.out : q.part, rows,
+                            q.wide, per, splits, q.transpose_out};
+            if (splits > 1) {              // a single range writes the result itself
+                rj[i] = ReduceJob{q.part, q.out, q.wide * rank, splits};
+                nb[i] = (int)((q.wide * rank / 4 + kTailThreads - 1) / kTailThreads);
+            }
+            const unsigned tiles = (unsigned)((q.wide + 127) / 128);
+            if (tiles > gx) gx = tiles;
+            if ((unsigned)splits > gy) gy = (unsigned)splits;
+        }
+        const dim3 grid(gx, gy, (unsigned)njobs), block(64 * kGradWaves);
+        if (rank <= 16) hipLaunchKernelGGL(lr_grad_kernel<1>, grid, block, 0, s, gj[0], gj[1], rank);
+        else if (rank <= 32) hipLaunchKernelGGL(lr_grad_kernel<2>, grid, block, 0, s, gj[0], gj[1], rank);
+        else hipLaunchKernelGGL(lr_grad_kernel<4>, grid, block, 0, s, gj[0], gj[1], rank);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
     }
-    if (sm) {
-        if (!lr_col_fwht_shape_ok(b, block_b)) return hipErrorInvalidValue;
-        // columns of S [b x rank]: vector (left block, column)
-        if (!fill_fwht_job(&j[n], sm, 0, sm_rot, block_b * rank, 1, rank, b / block_b, rank, block_b)) return hipErrorInvalidValue;
-        ++n;
+    // ---- the sums over the token ranges and the rotations of the thin operands, one launch
+    FwhtJob fj[2] = {};
+    if (rot) {
+        int n = 0;
+        if (rot->u) {
+            if (!lr_row_fwht_shape_ok(rot->m, rot->block_m)) return hipErrorInvalidValue;
+            // rows of U [rank x m]: vector (row, block of the row); no rotation: blocks of 64, conversion only
+            const int64_t blk = rot->block_m <= 1 ? 64 : rot->block_m;
+            if (!fill_fwht_job(&fj[n], rot->u, 1, rot->u_rot, rot->m, blk, 1, rank, rot->m / blk, blk)) return hipErrorInvalidValue;
+            if (rot->block_m <= 1) { fj[n].log_p = -1; fj[n].c_norm = 1.0f; }
+            fj[n].dst_a = 1; fj[n].dst_b = blk * rank; fj[n].dst_e = rank;       // transposed: element (col, r) at col * rank + r
+            ++n;
+        }
+        if (rot->sm) {
+            if (!lr_col_fwht_shape_ok(rot->b, rot->block_b)) return hipErrorInvalidValue;
+            // columns of S [b x rank]: vector (left block, column)
+            if (!fill_fwht_job(&fj[n], rot->sm, 0, rot->sm_rot, rot->block_b * rank, 1, rank, rot->b / rot->block_b, rank,
+                               rot->block_b))
+                return hipErrorInvalidValue;
+            ++n;
+        }
     }
-    if (n == 0) return hipSuccess;
-    if (n == 1) j[1] = j[0], j[1].vectors = 0;
-    hipLaunchKernelGGL(lr_small_fwht_kernel, dim3((unsigned)(j[0].vectors + j[1].vectors)), dim3(kSmallFwhtThreads), 0, s, j[0],
-                       j[1]);
+    const int64_t blocks = (int64_t)nb[0] + nb[1] + fj[0].vectors + fj[1].vectors;
+    if (blocks == 0) return hipSuccess;
+    if (blocks > 0x7FFFFFFF) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(lr_tail_kernel, dim3((unsigned)blocks), dim3(kTailThreads), 0, s, rj[0], rj[1], nb[0], nb[1], fj[0], fj[1]);
     return hipGetLastError();
 }
 
