@@ -24,7 +24,7 @@ struct RowArgs {
     int log_block;           // log2 of the Hadamard block, 0 = no rotation
     int kron_m;              // 0, or 28: the block is 28 * 2^log_block elements, rotated by H_{2^log_block} (x) H_28
     float in_mul;            // IN_F32 only: every element is multiplied by this once when it is loaded; 0 = no multiply
-    int left_top;            // launch_row_left_top only: number of top strides of the left-hand rotation still to run (1..4)
+    int left_top;            // launch_row_left_top only: number of top strides of the left-hand rotation still to run (1..5)
     // One scale per tensor (OUT_Q8 only): amax_only writes each row's absmax to out_scale and no codes; given_amax
     // (device scalar) replaces the row's own absmax.  post_scale (IN_I32 only, device scalar) is multiplied in after
     // pre_scale.  All three apply to both matrices of a batched launch.
@@ -55,7 +55,7 @@ hipError_t launch_row_transform(const RowArgs& a, InKind in, OutKind out, hipStr
 // rotation of block 256 << left_top have run except the top left_top ones; the kernel runs those (the 2^left_top rows
 // they mix sit in the wavefronts of one workgroup and meet in LDS), multiplies by in_mul, un-rotates each row in blocks
 // of 2^log_block and stores bf16 / fp32.  row_left_top_ok: the shapes it takes (log_block 9..12 dividing cols,
-// left_top 1..4, rows a multiple of the left block).
+// left_top 1..4, or 5 with log_block <= 11, rows a multiple of the left block).
 bool row_left_top_ok(int64_t rows, int64_t cols, int log_block, int left_top);
 hipError_t launch_row_left_top(const RowArgs& a, OutKind out, hipStream_t s);
 bool row_kron_shape_ok(int64_t cols, int64_t block);

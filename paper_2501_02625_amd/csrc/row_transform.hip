@@ -541,27 +541,36 @@ hipError_t launch_by_seg(const RowArgs& a, hipStream_t s) {
 // strides of the left-hand rotation (256, 512, ...) combine.  Stage st pairs wavefront t with t ^ 2^st through LDS (the
 // lower row takes a + b, the upper one a - b), ascending; then the wavefront has its row of the left-rotated matrix in
 // registers, in the layout of the row kernel, and goes on as that kernel does.
+// TOP == 5 (segments up to 2048 columns): the 32 rows sit two to a wavefront, rows t * 256 + q and (t + 16) * 256 + q of the
+// block of 8192; the first four of the five strides go through LDS as before, for both rows, and the last one (4096 rows)
+// pairs the wavefront's own two rows in registers.
 template <int LOGSEG, int OUT, int TOP>
-__global__ void __launch_bounds__(64 << TOP, LOGSEG >= 12 ? 4 : 8)
+__global__ void __launch_bounds__(TOP >= 5 ? 1024 : (64 << TOP), (LOGSEG >= 12 || TOP >= 5) ? 4 : 8)
 row_left_top_kernel(RowArgs a, int segs, float c_norm) {
     constexpr int LOGE = 2, EPL = 4;
     constexpr int VPL = 1 << (LOGSEG - 6);
     constexpr int NCH = VPL / EPL;
     constexpr int SEG = 1 << LOGSEG;
+    constexpr int NR = TOP >= 5 ? 2 : 1;                    // rows per wavefront
+    constexpr int XT = TOP >= 5 ? 4 : TOP;                  // strides that go through LDS
+    static_assert(TOP <= 5 && (TOP < 5 || LOGSEG <= 11), "32 rows of 4096 columns do not fit a compute unit");
     extern __shared__ __align__(16) float s_exch[];        // exchange buffer of the stages across wavefronts
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t g = (int64_t)blockIdx.x / segs;                 // group of 2^TOP rows: g = blk * 256 + q
     const int seg = (int)((int64_t)blockIdx.x % segs);
-    const int64_t row = ((g >> 8) << (8 + TOP)) + ((int64_t)wave << 8) + (g & 255);
+    const int64_t row0 = ((g >> 8) << (8 + TOP)) + ((int64_t)wave << 8) + (g & 255);
     const int64_t kbase = (int64_t)seg * SEG + (int64_t)lane * EPL;
 
-    float v[VPL];
-    const float* src = reinterpret_cast<const float*>(a.in) + row * a.ld_in + kbase;
+    float v[NR][VPL];
 #pragma unroll
-    for (int c = 0; c < NCH; ++c) {
-        const float4 q = *reinterpret_cast<const float4*>(src + c * 64 * EPL);
-        v[c * EPL + 0] = q.x; v[c * EPL + 1] = q.y; v[c * EPL + 2] = q.z; v[c * EPL + 3] = q.w;
+    for (int n = 0; n < NR; ++n) {
+        const float* src = reinterpret_cast<const float*>(a.in) + (row0 + (int64_t)n * 4096) * a.ld_in + kbase;
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) {
+            const float4 q = *reinterpret_cast<const float4*>(src + c * 64 * EPL);
+            v[n][c * EPL + 0] = q.x; v[n][c * EPL + 1] = q.y; v[n][c * EPL + 2] = q.z; v[n][c * EPL + 3] = q.w;
+        }
     }
     // Exchange buffer: [wavefront][value / 4][lane][4] (16-byte LDS accesses), HALF values per wavefront at a time so that
     // two workgroups fit one compute unit's LDS and one of them can load while the other exchanges.
@@ -569,48 +578,64 @@ row_left_top_kernel(RowArgs a, int segs, float c_norm) {
     float4* xb = reinterpret_cast<float4*>(s_exch);
     bool first_round = true;
 #pragma unroll
-    for (int st = 0; st < TOP; ++st) {
+    for (int st = 0; st < XT; ++st) {
         const bool upper = (wave >> st) & 1;
         const int pw = wave ^ (1 << st);
 #pragma unroll
-        for (int h0 = 0; h0 < VPL; h0 += HALF) {
-            if (!first_round) __syncthreads();   // everyone has read the previous round
-            first_round = false;
+        for (int n = 0; n < NR; ++n) {
 #pragma unroll
-            for (int r = 0; r < HALF; r += 4)
-                xb[(wave * (HALF / 4) + r / 4) * 64 + lane] = make_float4(v[h0 + r], v[h0 + r + 1], v[h0 + r + 2], v[h0 + r + 3]);
-            __syncthreads();
+            for (int h0 = 0; h0 < VPL; h0 += HALF) {
+                if (!first_round) __syncthreads();   // everyone has read the previous round
+                first_round = false;
 #pragma unroll
-            for (int r = 0; r < HALF; r += 4) {
-                const float4 p = xb[(pw * (HALF / 4) + r / 4) * 64 + lane];
-                v[h0 + r + 0] = upper ? p.x - v[h0 + r + 0] : v[h0 + r + 0] + p.x;
-                v[h0 + r + 1] = upper ? p.y - v[h0 + r + 1] : v[h0 + r + 1] + p.y;
-                v[h0 + r + 2] = upper ? p.z - v[h0 + r + 2] : v[h0 + r + 2] + p.z;
-                v[h0 + r + 3] = upper ? p.w - v[h0 + r + 3] : v[h0 + r + 3] + p.w;
+                for (int r = 0; r < HALF; r += 4)
+                    xb[(wave * (HALF / 4) + r / 4) * 64 + lane] =
+                        make_float4(v[n][h0 + r], v[n][h0 + r + 1], v[n][h0 + r + 2], v[n][h0 + r + 3]);
+                __syncthreads();
+#pragma unroll
+                for (int r = 0; r < HALF; r += 4) {
+                    const float4 p = xb[(pw * (HALF / 4) + r / 4) * 64 + lane];
+                    v[n][h0 + r + 0] = upper ? p.x - v[n][h0 + r + 0] : v[n][h0 + r + 0] + p.x;
+                    v[n][h0 + r + 1] = upper ? p.y - v[n][h0 + r + 1] : v[n][h0 + r + 1] + p.y;
+                    v[n][h0 + r + 2] = upper ? p.z - v[n][h0 + r + 2] : v[n][h0 + r + 2] + p.z;
+                    v[n][h0 + r + 3] = upper ? p.w - v[n][h0 + r + 3] : v[n][h0 + r + 3] + p.w;
+                }
             }
         }
     }
-    if (a.in_mul != 0.0f) {
+    if constexpr (NR == 2) {               // the last stride: the wavefront's own two rows
 #pragma unroll
-        for (int r = 0; r < VPL; ++r) v[r] *= a.in_mul;
+        for (int r = 0; r < VPL; ++r) {
+            const float x = v[0][r], y = v[NR - 1][r];
+            v[0][r] = x + y;
+            v[NR - 1][r] = x - y;
+        }
     }
-    // right-hand un-rotation of the row (block = segment), as in row_phase1
     const int bperm_addr = (lane ^ 32) << 2;
-    FwhtStages<VPL, LOGE, 0, LOGSEG>::run(v, LOGSEG, lane, bperm_addr);
     const float c_l = (__builtin_popcount(lane) & 1) ? -c_norm : c_norm;     // the sign the lane stages leave behind
 #pragma unroll
-    for (int r = 0; r < VPL; ++r) v[r] *= c_l;
+    for (int n = 0; n < NR; ++n) {
+        if (a.in_mul != 0.0f) {
+#pragma unroll
+            for (int r = 0; r < VPL; ++r) v[n][r] *= a.in_mul;
+        }
+        // right-hand un-rotation of the row (block = segment), as in row_phase1
+        FwhtStages<VPL, LOGE, 0, LOGSEG>::run(v[n], LOGSEG, lane, bperm_addr);
+#pragma unroll
+        for (int r = 0; r < VPL; ++r) v[n][r] *= c_l;
 
-    RowCtx x;
-    x.lane = lane; x.bperm_addr = bperm_addr; x.wave = wave; x.seg = seg; x.xbuf = s_exch;
-    x.row = row; x.kbase = kbase; x.row_ok = true;
-    row_phase2<LOGSEG, IN_F32, OUT, true>(a, x, v, 0.0f);
+        RowCtx x;
+        x.lane = lane; x.bperm_addr = bperm_addr; x.wave = wave; x.seg = seg; x.xbuf = s_exch;
+        x.row = row0 + (int64_t)n * 4096; x.kbase = kbase; x.row_ok = true;
+        row_phase2<LOGSEG, IN_F32, OUT, true>(a, x, v[n], 0.0f);
+    }
 }
 
 template <int LOGSEG, int OUT, int TOP>
 hipError_t launch_left_top(const RowArgs& a, hipStream_t s) {
     constexpr int VPL = 1 << (LOGSEG - 6);
-    constexpr int kLds = (1 << TOP) * (VPL > 16 ? VPL / 2 : VPL) * 64 * (int)sizeof(float);
+    constexpr int kWaves = TOP >= 5 ? 16 : (1 << TOP);
+    constexpr int kLds = kWaves * (VPL > 16 ? VPL / 2 : VPL) * 64 * (int)sizeof(float);
     static std::once_flag once;
     static hipError_t attr_result = hipSuccess;
     auto kern = row_left_top_kernel<LOGSEG, OUT, TOP>;
@@ -623,7 +648,7 @@ hipError_t launch_left_top(const RowArgs& a, hipStream_t s) {
     const int64_t blocks = (a.rows >> TOP) * segs;
     if (blocks <= 0 || blocks > 0x7FFFFFFF) return hipErrorInvalidValue;
     const float c_norm = (float)(1.0 / sqrt((double)(int64_t(1) << LOGSEG)));
-    hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(64 << TOP), kLds, s, a, segs, c_norm);
+    hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(64 * kWaves), kLds, s, a, segs, c_norm);
     return hipGetLastError();
 }
 
@@ -634,6 +659,9 @@ hipError_t launch_left_top_by_top(const RowArgs& a, hipStream_t s) {
         case 2: return launch_left_top<LOGSEG, OUT, 2>(a, s);
         case 3: return launch_left_top<LOGSEG, OUT, 3>(a, s);
         case 4: return launch_left_top<LOGSEG, OUT, 4>(a, s);
+        case 5:
+            if constexpr (LOGSEG <= 11) return launch_left_top<LOGSEG, OUT, 5>(a, s);
+            return hipErrorInvalidValue;
         default: return hipErrorInvalidValue;
     }
 }
@@ -652,7 +680,8 @@ hipError_t launch_left_top_by_seg(const RowArgs& a, hipStream_t s) {
 }  // namespace
 
 bool row_left_top_ok(int64_t rows, int64_t cols, int log_block, int left_top) {
-    if (log_block < 9 || log_block > 12 || left_top < 1 || left_top > 4) return false;
+    if (log_block < 9 || log_block > 12 || left_top < 1 || left_top > 5) return false;
+    if (left_top == 5 && log_block > 11) return false;      // 32 rows of 4096 columns do not fit a compute unit
     if (rows <= 0 || cols <= 0 || cols % (int64_t(1) << log_block) != 0) return false;
     return rows % (int64_t(256) << left_top) == 0;
 }

@@ -105,7 +105,10 @@ def test_small_layers_all_levels(b, m, n, level):
     (2048, 2048, 128, 0, 0, torch.bfloat16),       # three top strides, right block 2048
     (4096, 512, 64, 0, 0, torch.float32),          # four top strides, right block 512
     (1024, 1536, 192, 512, 512, torch.float32),    # two left blocks of 512 (one top stride), three right blocks of 512
-    (8192, 512, 64, 0, 0, torch.float32),          # left block 8192: five strides left, the strided pass takes them
+    (8192, 512, 64, 0, 0, torch.float32),          # left block 8192: five strides left, two rows per wavefront
+    (8192, 2048, 64, 0, 0, torch.bfloat16),        # the same with the widest segment that fits (2048)
+    (16384, 1024, 64, 0, 8192, torch.float32),     # two left blocks of 8192
+    (8192, 4096, 64, 0, 0, torch.float32),         # five strides and a 4096 block: the strided pass takes them
     (768, 1024, 128, 0, 0, torch.float32),         # b = 3 * 256: left block 256, nothing left after the epilogue
     (512, 4096, 64, 0, 0, torch.float32),          # one top stride, right block 4096 (64 values per lane)
     (4096, 4096, 128, 0, 0, torch.bfloat16),       # four top strides, right block 4096
