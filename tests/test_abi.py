@@ -254,6 +254,13 @@ def test_binding_refuses_missing_library(tmp_path):
         binding.load_library(str(tmp_path / "nope.so"))
 
 
+def test_bench_refuses_more_than_one_gpu():
+    """One GPU only: bench.py --gpus N with N > 1 exits with a message before it touches a device."""
+    import subprocess, sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 2 and "ONE GPU" in r.stderr
+
+
 def test_inputs_are_deterministic_and_shaped():
     import numpy as np
     from paper_2501_02625_amd import inputs
