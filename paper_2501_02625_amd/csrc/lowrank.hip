@@ -2,8 +2,8 @@
 // "Parameter Efficient Fine Tuning"; Appendix "LoRA-style Linear Module and HALO for PEFT"):
 //   T = X U^T,  S = E_Y V            (tall input times a thin matrix: lr_down_kernel, bf16 matrix instructions)
 //   G_V = E_Y^T T,  G_U = S^T X      (thin result, reduction over the tokens: lr_grad_kernel, summed up in lr_tail_kernel)
-// and the small helpers that bring V and U into the form the GEMM epilogue wants (rank-major; U rotated).  The additions
-// T V^T and S U themselves happen in the epilogue of the INT8 GEMM.  All inputs are bf16, every product accumulates in
+// and the rotations H S and (U H)^T of the thin operands that the epilogue of the E_X product wants (lr_tail_kernel).  The
+// additions T V^T and S U themselves happen in the epilogue of the INT8 GEMM.  All inputs are bf16, every product accumulates in
 // fp32 and the intermediates T and S stay fp32.  Every kernel here is bound by one read of its tall operand from HBM.
 #pragma clang fp contract(off)
 
